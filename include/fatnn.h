@@ -1,0 +1,158 @@
+/*
+ * fatnn.h -- C ABI of the MI355X (gfx950) ternary GEMM / convolution library.
+ *
+ * The library evaluates the reduced-complexity ternary inner product of FATNN
+ * (arXiv 2008.05101, Section 3.3): two ternary vectors are stored in the 2-bit
+ * codec of Table 1 (popcount(codec) = value + 1), multiplied with a handful of
+ * bitwise operations (Eq. 4-7) and accumulated with one popcount per packed word
+ * (Eq. 3, Algorithm 1), instead of the four binary inner products that the
+ * conventional decomposition (Eq. 2 with two bits per operand) needs.
+ *
+ * Conventions common to every entry point
+ *   - Tensors are addressed through plain pointers.  Every tensor pointer is a
+ *     DEVICE pointer owned by the caller; the library never allocates, frees or
+ *     keeps it.  `dims` arrays and scalars are host values.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued asynchronously on it; nothing synchronises.
+ *   - The return value is a fatnn_status.  Argument errors are found on the
+ *     host before any GPU call, so they are reported even with no GPU present.
+ *     No entry point throws or aborts.
+ *   - Inputs are LEVEL INDICES l in {0,1,2} (int8), l = popcount of the paper's
+ *     codec.  Weights mean l-1 in {-1,0,+1}.  Activations mean l-1 (FATNN_SYM) or
+ *     l in {0,1,2} (FATNN_RELU, the paper's second constraint in Section 3.3).
+ *   - Zero-sized problems (no rows / no columns / no batch) succeed and launch
+ *     nothing.  K (or Cin) must be at least 1.
+ *
+ * Packed layout ("plane words"): a row of K elements becomes Kw = ceil(K/32)
+ * pairs of 32-bit words; bit e of a pair's words belongs to element 32*kw + e.
+ *     activations: .x = (l == 2),  .y = (l >= 1)      the two codec bits of Table 1
+ *                                                     with 0 spelled 01
+ *     weights:     .x = (l == 2),  .y = (l != 1)      sign bit and non-zero bit; the
+ *                                                     latter is the complement of
+ *                                                     Eq. 6's mask, fixed after
+ *                                                     training like the paper's
+ *   Tail elements (k >= K) are packed as the value 0.  A packed weight buffer
+ *   ends with two int32 per row (count of non-zero weights, count of +1
+ *   weights), from which the kernels form Eq. 3's "- N" term and the ReLU-mode
+ *   constant ("add a copy of the weights", Section 3.3).
+ */
+#ifndef FATNN_H
+#define FATNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FATNN_OK = 0,
+    FATNN_ERR_NULL = -1,        /* a required pointer is NULL                         */
+    FATNN_ERR_SHAPE = -2,       /* negative / zero / inconsistent dimension           */
+    FATNN_ERR_LEVEL = -3,       /* reserved for callers that read back *n_invalid     */
+    FATNN_ERR_ALIGN = -4,       /* pointer not aligned as documented                  */
+    FATNN_ERR_SIZE = -5,        /* buffer too small, or dimension beyond the limits   */
+    FATNN_ERR_UNSUPPORTED = -6, /* valid but not implemented (never a wrong answer)   */
+    FATNN_ERR_HIP = -7          /* the HIP runtime refused a launch                   */
+} fatnn_status;
+
+enum { FATNN_WEIGHT = 0, FATNN_ACT = 1 };                 /* role     */
+enum { FATNN_SYM = 0, FATNN_RELU = 1 };                   /* act_mode */
+enum {                                                    /* layout of a level tensor, dims[4]        */
+    FATNN_ROWMAJOR_K = 0, /* dims = {rows, K, 1, 1}: [rows][K], K contiguous                          */
+    FATNN_NHWC = 1,       /* dims = {B, H, W, C}: rows = B*H*W pixels, K = C   (activations)          */
+    FATNN_OHWI = 2,       /* dims = {O, R, S, C}: rows = O, K = R*S*C, c innermost (conv weights)     */
+    FATNN_OIHW = 3,       /* dims = {O, C, R, S}: same packed result as OHWI (gathering, slow path)   */
+    FATNN_NCHW = 4        /* dims = {B, C, H, W}: same packed result as NHWC (gathering, slow path)   */
+};
+enum { FATNN_BASIS_TERNARY = 0, FATNN_BASIS_UNIFORM = 1 };/* two-bit basis, see fatnn_twobit_gemm     */
+
+/* Largest supported extents: rows, columns < 2^31; K <= 2^24 (keeps |C| <= 2K exact in fp32 too). */
+#define FATNN_MAX_K (1 << 24)
+
+/* ceil(K / 32): plane-word pairs per packed row.  Returns -1 for K < 1. */
+int64_t fatnn_words_per_row(int64_t K);
+
+/* Bytes of a packed buffer of `rows` rows of K elements.  role = FATNN_WEIGHT adds
+ * the per-row constants (see file header).  Returns 0 on invalid arguments.
+ * Layout: rows*Kw pairs of uint32, then (weights only) at the next multiple of
+ * 256 bytes int32 nnz[rows] followed by int32 npos[rows]. */
+size_t fatnn_packed_bytes(int role, int64_t rows, int64_t K);
+
+/* Byte offset of the per-row constants inside a packed weight buffer. */
+size_t fatnn_weight_consts_offset(int64_t rows, int64_t K);
+
+/*
+ * Algorithm 1, step 1 (data packing), from level indices.
+ *   levels        device, int8, laid out as `layout` / `dims` say.
+ *   role          FATNN_WEIGHT or FATNN_ACT (selects the plane meaning above; for
+ *                 weights the per-row constants are computed too -- the
+ *                 precomputation the paper does once after training, Section 3.3).
+ *   packed        device, 16-byte aligned, at least fatnn_packed_bytes() bytes.
+ *   n_invalid     device int32 or NULL.  The number of elements outside {0,1,2}
+ *                 is ADDED to it (the caller zeroes it); such elements are packed
+ *                 as the value 0.  The paper's first constraint makes them an
+ *                 input error; a caller that cares reads the counter back.
+ * NHWC / OHWI / OIHW / NCHW need C to be a multiple of 32 so that every pixel /
+ * filter tap starts on a word boundary.
+ */
+int fatnn_pack_ternary(const int8_t *levels, int layout, const int64_t dims[4], int role,
+                       void *packed, size_t packed_bytes, int32_t *n_invalid, void *stream);
+
+/*
+ * Ternary GEMM through Eq. 3:  C[m][n] = sum_k w[m][k] * a[n][k].
+ *   Wp            packed weights  [M][Kw] (+ constants), from fatnn_pack_ternary(role WEIGHT)
+ *   Ap            packed activations [N][Kw], from fatnn_pack_ternary(role ACT)
+ *   C             int32 [M][ldc], ldc >= N, or NULL
+ *   Cf            fp32  [M][ldcf], ldcf >= N, or NULL:  Cf = scale[m] * float(C) (+ bias[m]);
+ *                 the single high-precision coefficient of the paper's first
+ *                 constraint, per output channel.  scale is required when Cf is
+ *                 given; bias may be NULL.  At least one of C, Cf must be given.
+ */
+int fatnn_ternary_gemm(const void *Wp, const void *Ap, int64_t M, int64_t N, int64_t K, int act_mode,
+                       int32_t *C, int64_t ldc, const float *scale, const float *bias, float *Cf,
+                       int64_t ldcf, void *stream);
+
+/*
+ * Ternary convolution as an implicit GEMM (Supplementary S1: im2col + gemm, here
+ * without materialising the matrix).
+ *   Wp            packed weights from layout OHWI/OIHW: [Cout][R*S*Cin/32] (+ constants)
+ *   Xp            packed activations from layout NHWC/NCHW: [B][H][W][Cin/32]
+ *   Y, Yf         int32 / fp32 NHWC outputs [B][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
+ *   Padding is the VALUE 0 in either act_mode.
+ * Supported: R = S in {1, 3}, stride in {1, 2}, pad in {0, 1} with pad <= R/2,
+ * Cin a multiple of 32; anything else returns FATNN_ERR_UNSUPPORTED.
+ */
+int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                         int64_t Cout, int R, int S, int stride, int pad, int act_mode, int32_t *Y,
+                         const float *scale, const float *bias, float *Yf, void *stream);
+
+/*
+ * Conventional two-bit path (Eq. 2 with two bit-planes per operand and the binary
+ * inner product of Eq. 1): four logic operations and four popcounts per packed
+ * word pair where Eq. 3 needs two and two.  It exists so the paper's O(4N) ->
+ * O(2N) claim (Remark 1) can be measured on the same chip with the same tiling.
+ *
+ * Codes q = 2*b1 + b0 in {0,1,2,3}; plane words .x = b1, .y = b0; tail bits 0.
+ * The value of a code is  alpha0*(2*b0-1) + alpha1*(2*b1-1):
+ *   FATNN_BASIS_TERNARY  alpha = (1/2, 1/2): 00,01,10,11 -> -1,0,0,+1 (Table 1's codec)
+ *   FATNN_BASIS_UNIFORM  alpha = (1, 2):     00,01,10,11 -> -3,-1,+1,+3
+ * C[m][n] = sum_k value(w) * value(a), int32.
+ */
+int fatnn_pack_twobit(const int8_t *codes, int layout, const int64_t dims[4], void *packed,
+                      size_t packed_bytes, int32_t *n_invalid, void *stream);
+int fatnn_twobit_gemm(const void *Wp, const void *Ap, int64_t M, int64_t N, int64_t K, int basis,
+                      int32_t *C, int64_t ldc, void *stream);
+/* TERNARY basis only (the padded taps need a code of value 0). */
+int fatnn_twobit_conv2d(const void *Wp, const void *Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                        int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t *Y,
+                        void *stream);
+
+const char *fatnn_status_str(int status);
+int fatnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FATNN_H */

@@ -1,0 +1,12 @@
+"""MI355X-native ternary GEMM / convolution (FATNN, arXiv 2008.05101, Section 3.3).
+
+Thin Python binding over the C-ABI library ``libfatnn.so`` (HIP, gfx950 only).
+Importing this package does not load the library; the first call does, and it
+raises if the library has not been built (``python -m paper_2008_05101_amd.build``).
+There is no CPU fallback.
+"""
+from .binding import (  # noqa: F401
+    ACT, BASIS_TERNARY, BASIS_UNIFORM, NCHW, NHWC, OHWI, OIHW, RELU, ROWMAJOR_K, SYM, WEIGHT,
+    FatnnError, lib, pack_ternary, pack_twobit, packed_bytes, status_str, ternary_conv2d, ternary_gemm,
+    twobit_conv2d, twobit_gemm, weight_consts_offset, words_per_row,
+)

@@ -1,0 +1,213 @@
+"""ctypes binding of include/fatnn.h.  Argument marshalling only: every step of the
+path (packing, multiply-accumulate, epilogue) runs in the HIP kernels.  torch is
+used for device memory and the current stream, nothing else."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfatnn.so")
+
+WEIGHT, ACT = 0, 1
+SYM, RELU = 0, 1
+ROWMAJOR_K, NHWC, OHWI, OIHW, NCHW = 0, 1, 2, 3, 4
+BASIS_TERNARY, BASIS_UNIFORM = 0, 1
+
+EXPORTS = [
+    "fatnn_words_per_row", "fatnn_packed_bytes", "fatnn_weight_consts_offset", "fatnn_pack_ternary",
+    "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
+    "fatnn_twobit_conv2d", "fatnn_status_str", "fatnn_version",
+]
+
+
+class FatnnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_str(status)} (status {status})")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libfatnn.so; fails loudly if it is not built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2008_05101_amd.build` "
+                "(there is no CPU fallback)")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+        l.fatnn_words_per_row.argtypes = [i64]
+        l.fatnn_words_per_row.restype = i64
+        l.fatnn_packed_bytes.argtypes = [i32, i64, i64]
+        l.fatnn_packed_bytes.restype = sz
+        l.fatnn_weight_consts_offset.argtypes = [i64, i64]
+        l.fatnn_weight_consts_offset.restype = sz
+        dims4 = ctypes.POINTER(i64)
+        l.fatnn_pack_ternary.argtypes = [vp, i32, dims4, i32, vp, sz, vp, vp]
+        l.fatnn_pack_twobit.argtypes = [vp, i32, dims4, vp, sz, vp, vp]
+        l.fatnn_ternary_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, i64, vp]
+        l.fatnn_ternary_conv2d.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        l.fatnn_twobit_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp]
+        l.fatnn_twobit_conv2d.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
+        l.fatnn_status_str.argtypes = [i32]
+        l.fatnn_status_str.restype = ctypes.c_char_p
+        l.fatnn_version.restype = i32
+        _lib = l
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().fatnn_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise FatnnError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must be {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def words_per_row(K: int) -> int:
+    return int(lib().fatnn_words_per_row(K))
+
+
+def packed_bytes(role: int, rows: int, K: int) -> int:
+    return int(lib().fatnn_packed_bytes(role, rows, K))
+
+
+def weight_consts_offset(rows: int, K: int) -> int:
+    return int(lib().fatnn_weight_consts_offset(rows, K))
+
+
+def _rows_k(layout: int, dims: Sequence[int]) -> Tuple[int, int]:
+    d = list(dims)
+    if layout == ROWMAJOR_K:
+        return d[0], d[1]
+    if layout == NHWC:
+        return d[0] * d[1] * d[2], d[3]
+    if layout == OHWI:
+        return d[0], d[1] * d[2] * d[3]
+    if layout == OIHW:
+        return d[0], d[1] * d[2] * d[3]
+    if layout == NCHW:
+        return d[0] * d[2] * d[3], d[1]
+    raise ValueError("unknown layout")
+
+
+def _dims4(layout: int, levels: torch.Tensor):
+    shape = list(levels.shape)
+    if layout == ROWMAJOR_K:
+        if len(shape) != 2:
+            raise ValueError("ROWMAJOR_K wants a 2-D tensor")
+        shape = shape + [1, 1]
+    elif len(shape) != 4:
+        raise ValueError("layout wants a 4-D tensor")
+    return (ctypes.c_int64 * 4)(*shape), shape
+
+
+def pack_ternary(levels: torch.Tensor, role: int, layout: int = ROWMAJOR_K,
+                 out: Optional[torch.Tensor] = None, n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fatnn_pack_ternary: int8 level tensor -> packed plane words (uint8 buffer)."""
+    levels = _dev(levels, torch.int8, "levels")
+    dims, shape = _dims4(layout, levels)
+    rows, K = _rows_k(layout, shape)
+    nbytes = packed_bytes(role, rows, K) if K >= 1 else 0
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=levels.device)
+    _check(lib().fatnn_pack_ternary(_ptr(levels), layout, dims, role, _ptr(out), out.numel(),
+                                    _ptr(n_invalid), _stream()), "fatnn_pack_ternary")
+    return out
+
+
+def pack_twobit(codes: torch.Tensor, layout: int = ROWMAJOR_K, out: Optional[torch.Tensor] = None,
+                n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+    codes = _dev(codes, torch.int8, "codes")
+    dims, shape = _dims4(layout, codes)
+    rows, K = _rows_k(layout, shape)
+    nbytes = packed_bytes(ACT, rows, K) if K >= 1 else 0
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=codes.device)
+    _check(lib().fatnn_pack_twobit(_ptr(codes), layout, dims, _ptr(out), out.numel(), _ptr(n_invalid),
+                                   _stream()), "fatnn_pack_twobit")
+    return out
+
+
+def ternary_gemm(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, act_mode: int = SYM,
+                 out: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
+                 bias: Optional[torch.Tensor] = None, out_f: Optional[torch.Tensor] = None,
+                 want_int: bool = True):
+    """fatnn_ternary_gemm.  Returns (C int32 [M][N] or None, Cf fp32 [M][N] or None)."""
+    if out is None and want_int:
+        out = torch.empty((M, N), dtype=torch.int32, device=Wp.device)
+    if scale is not None and out_f is None:
+        out_f = torch.empty((M, N), dtype=torch.float32, device=Wp.device)
+    ldc = out.stride(0) if out is not None and out.dim() == 2 and M > 0 else N
+    ldcf = out_f.stride(0) if out_f is not None and out_f.dim() == 2 and M > 0 else N
+    _check(lib().fatnn_ternary_gemm(_ptr(Wp), _ptr(Ap), M, N, K, act_mode, _ptr(out), max(ldc, N), _ptr(scale),
+                                    _ptr(bias), _ptr(out_f), max(ldcf, N), _stream()), "fatnn_ternary_gemm")
+    return out, out_f
+
+
+def _conv_out_hw(H: int, W: int, R: int, S: int, stride: int, pad: int) -> Tuple[int, int]:
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+
+
+def ternary_conv2d(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H: int, W: int, Cout: int,
+                   R: int = 3, S: int = 3, stride: int = 1, pad: int = 1, act_mode: int = RELU,
+                   out: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
+                   bias: Optional[torch.Tensor] = None, out_f: Optional[torch.Tensor] = None,
+                   want_int: bool = True):
+    """fatnn_ternary_conv2d.  Returns (Y int32 NHWC or None, Yf fp32 NHWC or None)."""
+    Ho, Wo = _conv_out_hw(H, W, R, S, stride, pad)
+    if out is None and want_int:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.int32, device=Wp.device)
+    if scale is not None and out_f is None:
+        out_f = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=Wp.device)
+    _check(lib().fatnn_ternary_conv2d(_ptr(Wp), _ptr(Xp), B, Cin, H, W, Cout, R, S, stride, pad, act_mode,
+                                      _ptr(out), _ptr(scale), _ptr(bias), _ptr(out_f), _stream()),
+           "fatnn_ternary_conv2d")
+    return out, out_f
+
+
+def twobit_gemm(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, basis: int = BASIS_TERNARY,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=Wp.device)
+    ldc = out.stride(0) if out.dim() == 2 and M > 0 else N
+    _check(lib().fatnn_twobit_gemm(_ptr(Wp), _ptr(Ap), M, N, K, basis, _ptr(out), max(ldc, N), _stream()),
+           "fatnn_twobit_gemm")
+    return out
+
+
+def twobit_conv2d(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H: int, W: int, Cout: int,
+                  R: int = 3, S: int = 3, stride: int = 1, pad: int = 1, basis: int = BASIS_TERNARY,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    Ho, Wo = _conv_out_hw(H, W, R, S, stride, pad)
+    if out is None:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.int32, device=Wp.device)
+    _check(lib().fatnn_twobit_conv2d(_ptr(Wp), _ptr(Xp), B, Cin, H, W, Cout, R, S, stride, pad, basis,
+                                     _ptr(out), _stream()), "fatnn_twobit_conv2d")
+    return out

@@ -1,0 +1,319 @@
+// Host layer of the C ABI declared in include/fatnn.h: argument checks (all done
+// before the first GPU call, so they work with no GPU present), buffer layout, and
+// the choice of kernel.  Nothing here computes.
+#include "../../include/fatnn.h"
+#include "fatnn_device.h"
+
+using namespace fatnn;
+
+namespace {
+
+constexpr int64_t kMaxRows = 0x7FFFFFFFLL;
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+struct PackShape {
+    int64_t rows, K;
+    bool gather;
+    GatherDesc g;
+};
+
+// Turns (layout, dims) into rows x K plus, for the non-contiguous layouts, the gather rule.
+int pack_shape(int layout, const int64_t dims[4], PackShape* out) {
+    for (int i = 0; i < 4; ++i)
+        if (dims[i] < 0) return FATNN_ERR_SHAPE;
+    PackShape s{};
+    switch (layout) {
+        case FATNN_ROWMAJOR_K:
+            s.rows = dims[0];
+            s.K = dims[1];
+            s.gather = false;
+            break;
+        case FATNN_NHWC:
+        case FATNN_OHWI: {
+            const int64_t C = dims[3];
+            if (C < 1) return FATNN_ERR_SHAPE;
+            if (C % 32 != 0) return FATNN_ERR_UNSUPPORTED;
+            if (layout == FATNN_NHWC) {
+                if (dims[1] > kMaxRows || dims[2] > kMaxRows) return FATNN_ERR_SIZE;
+                if (dims[0] != 0 && dims[1] * dims[2] > kMaxRows / (dims[0] > 0 ? dims[0] : 1)) return FATNN_ERR_SIZE;
+                s.rows = dims[0] * dims[1] * dims[2];
+                s.K = C;
+            } else {
+                if (dims[1] < 1 || dims[2] < 1) return FATNN_ERR_SHAPE;
+                if (dims[1] > 64 || dims[2] > 64) return FATNN_ERR_SIZE;
+                s.rows = dims[0];
+                s.K = dims[1] * dims[2] * C;
+            }
+            s.gather = false;
+            break;
+        }
+        case FATNN_OIHW: {
+            const int64_t O = dims[0], C = dims[1], R = dims[2], S = dims[3];
+            if (C < 1 || R < 1 || S < 1) return FATNN_ERR_SHAPE;
+            if (C % 32 != 0) return FATNN_ERR_UNSUPPORTED;
+            if (R > 64 || S > 64) return FATNN_ERR_SIZE;
+            s.rows = O;
+            s.K = R * S * C;
+            s.gather = true;
+            // row = o: offset o*C*R*S;  k = (r*S+s)*C + c: offset (r*S+s) + c*R*S
+            s.g.n1 = 1; s.g.rs0 = C * R * S; s.g.rs1 = 0;
+            s.g.C = C; s.g.ks0 = 1; s.g.ks1 = R * S;
+            break;
+        }
+        case FATNN_NCHW: {
+            const int64_t B = dims[0], C = dims[1], H = dims[2], W = dims[3];
+            if (C < 1) return FATNN_ERR_SHAPE;
+            if (C % 32 != 0) return FATNN_ERR_UNSUPPORTED;
+            if (H > kMaxRows || W > kMaxRows) return FATNN_ERR_SIZE;
+            if (B != 0 && H * W > kMaxRows / B) return FATNN_ERR_SIZE;
+            s.rows = B * H * W;
+            s.K = C;
+            s.gather = true;
+            // row = b*(H*W) + hw: offset b*C*H*W + hw;  k = c: offset c*H*W
+            s.g.n1 = (H * W > 0) ? H * W : 1; s.g.rs0 = C * H * W; s.g.rs1 = 1;
+            s.g.C = C; s.g.ks0 = 0; s.g.ks1 = H * W;
+            break;
+        }
+        default:
+            return FATNN_ERR_UNSUPPORTED;
+    }
+    if (s.K < 1) return FATNN_ERR_SHAPE;
+    if (s.K > FATNN_MAX_K || s.rows > kMaxRows) return FATNN_ERR_SIZE;
+    *out = s;
+    return FATNN_OK;
+}
+
+int pack_common(const int8_t* levels, int layout, const int64_t dims[4], int kind, void* packed,
+                size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    if (dims == nullptr) return FATNN_ERR_NULL;
+    PackShape s;
+    int rc = pack_shape(layout, dims, &s);
+    if (rc != FATNN_OK) return rc;
+    const int role = (kind == PACK_WEIGHT) ? FATNN_WEIGHT : FATNN_ACT;
+    if (s.rows == 0) return FATNN_OK;
+    if (levels == nullptr || packed == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(packed, 16)) return FATNN_ERR_ALIGN;
+    if (n_invalid != nullptr && !aligned(n_invalid, 4)) return FATNN_ERR_ALIGN;
+    if (packed_bytes < fatnn_packed_bytes(role, s.rows, s.K)) return FATNN_ERR_SIZE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    plane2* out = reinterpret_cast<plane2*>(packed);
+    int lrc = s.gather ? launch_pack_gather(levels, s.rows, s.K, s.g, kind, out, n_invalid, st)
+                       : launch_pack_contiguous(levels, s.rows, s.K, kind, out, n_invalid, st);
+    if (lrc != 0) return FATNN_ERR_HIP;
+    if (kind == PACK_WEIGHT) {
+        const int64_t Kw = fatnn_words_per_row(s.K);
+        int32_t* consts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(packed) +
+                                                     fatnn_weight_consts_offset(s.rows, s.K));
+        if (launch_row_constants(out, s.rows, Kw, consts, consts + s.rows, st) != 0) return FATNN_ERR_HIP;
+    }
+    return FATNN_OK;
+}
+
+int check_gemm_dims(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 1) return FATNN_ERR_SHAPE;
+    if (M > kMaxRows || N > kMaxRows || K > FATNN_MAX_K) return FATNN_ERR_SIZE;
+    return FATNN_OK;
+}
+
+struct ConvShape {
+    int64_t Ho, Wo, N, K;
+};
+
+int check_conv_dims(int64_t B, int64_t Cin, int64_t H, int64_t W, int64_t Cout, int R, int S, int stride,
+                    int pad, ConvShape* cs) {
+    if (B < 0 || Cin < 1 || H < 1 || W < 1 || Cout < 0 || R < 1 || S < 1 || stride < 1 || pad < 0)
+        return FATNN_ERR_SHAPE;
+    if (!(R == S && (R == 1 || R == 3))) return FATNN_ERR_UNSUPPORTED;
+    if (!(stride == 1 || stride == 2)) return FATNN_ERR_UNSUPPORTED;
+    if (!(pad == 0 || pad == 1) || pad > R / 2) return FATNN_ERR_UNSUPPORTED;
+    if (Cin % 32 != 0) return FATNN_ERR_UNSUPPORTED;
+    if (H + 2 * pad < R || W + 2 * pad < S) return FATNN_ERR_SHAPE;
+    if (H > 65535 || W > 65535 || Cout > kMaxRows) return FATNN_ERR_SIZE;
+    cs->Ho = (H + 2 * pad - R) / stride + 1;
+    cs->Wo = (W + 2 * pad - S) / stride + 1;
+    cs->K = (int64_t)R * S * Cin;
+    if (cs->K > FATNN_MAX_K) return FATNN_ERR_SIZE;
+    if (B != 0 && cs->Ho * cs->Wo > kMaxRows / B) return FATNN_ERR_SIZE;
+    if (B != 0 && H * W > kMaxRows / B) return FATNN_ERR_SIZE;
+    cs->N = B * cs->Ho * cs->Wo;
+    return FATNN_OK;
+}
+
+void set_ternary_consts(GemmParams& p, const void* Wp, int64_t M, int64_t K, int act_mode) {
+    const int32_t* consts = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(Wp) +
+                                                             fatnn_weight_consts_offset(M, K));
+    // symmetric: x.w = nnz - P'.  ReLU: values are one higher, which adds the sum of
+    // the weights (npos - nneg): nnz + npos - nneg = 2 * npos.
+    if (act_mode == FATNN_RELU) {
+        p.rowc = consts + M;
+        p.cmul = 2;
+    } else {
+        p.rowc = consts;
+        p.cmul = 1;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t fatnn_words_per_row(int64_t K) { return K < 1 ? -1 : (K + 31) / 32; }
+
+size_t fatnn_weight_consts_offset(int64_t rows, int64_t K) {
+    if (rows < 0 || K < 1) return 0;
+    return round_up((size_t)rows * (size_t)fatnn_words_per_row(K) * sizeof(plane2), 256);
+}
+
+size_t fatnn_packed_bytes(int role, int64_t rows, int64_t K) {
+    if (rows < 0 || K < 1 || (role != FATNN_WEIGHT && role != FATNN_ACT)) return 0;
+    const size_t words = (size_t)rows * (size_t)fatnn_words_per_row(K) * sizeof(plane2);
+    if (role == FATNN_ACT) return words;
+    return fatnn_weight_consts_offset(rows, K) + round_up((size_t)rows * 2 * sizeof(int32_t), 256);
+}
+
+int fatnn_pack_ternary(const int8_t* levels, int layout, const int64_t dims[4], int role, void* packed,
+                       size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    if (role != FATNN_WEIGHT && role != FATNN_ACT) return FATNN_ERR_UNSUPPORTED;
+    return pack_common(levels, layout, dims, role == FATNN_WEIGHT ? PACK_WEIGHT : PACK_ACT, packed,
+                       packed_bytes, n_invalid, stream);
+}
+
+int fatnn_pack_twobit(const int8_t* codes, int layout, const int64_t dims[4], void* packed,
+                      size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    return pack_common(codes, layout, dims, PACK_TWOBIT, packed, packed_bytes, n_invalid, stream);
+}
+
+int fatnn_ternary_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int act_mode,
+                       int32_t* C, int64_t ldc, const float* scale, const float* bias, float* Cf,
+                       int64_t ldcf, void* stream) {
+    int rc = check_gemm_dims(M, N, K);
+    if (rc != FATNN_OK) return rc;
+    if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return FATNN_OK;   // nothing to compute: output pointers may be null
+    if (C == nullptr && Cf == nullptr) return FATNN_ERR_NULL;
+    if (Cf != nullptr && scale == nullptr) return FATNN_ERR_NULL;
+    if (C != nullptr && ldc < N) return FATNN_ERR_SHAPE;
+    if (Cf != nullptr && ldcf < N) return FATNN_ERR_SHAPE;
+    if (Wp == nullptr || Ap == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(Wp, 16) || !aligned(Ap, 16) || !aligned(C, 4) || !aligned(Cf, 4) || !aligned(scale, 4) ||
+        !aligned(bias, 4))
+        return FATNN_ERR_ALIGN;
+    GemmParams p{};
+    p.W = reinterpret_cast<const plane2*>(Wp);
+    p.A = reinterpret_cast<const plane2*>(Ap);
+    set_ternary_consts(p, Wp, M, K, act_mode);
+    p.K = (int32_t)K;
+    p.M = (int32_t)M;
+    p.N = (int32_t)N;
+    p.Kw = (int32_t)fatnn_words_per_row(K);
+    p.C = C; p.ldc_m = ldc; p.ldc_n = 1;
+    p.Cf = Cf; p.ldf_m = ldcf; p.ldf_n = 1;
+    p.scale = scale; p.bias = bias;
+    p.is_conv = 0;
+    return launch_gemm(p, OP_TERNARY, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+}
+
+int fatnn_ternary_conv2d(const void* Wp, const void* Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                         int64_t Cout, int R, int S, int stride, int pad, int act_mode, int32_t* Y,
+                         const float* scale, const float* bias, float* Yf, void* stream) {
+    ConvShape cs;
+    int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
+    if (rc != FATNN_OK) return rc;
+    if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
+    if (B == 0 || Cout == 0) return FATNN_OK;
+    if (Y == nullptr && Yf == nullptr) return FATNN_ERR_NULL;
+    if (Yf != nullptr && scale == nullptr) return FATNN_ERR_NULL;
+    if (Wp == nullptr || Xp == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(Wp, 16) || !aligned(Xp, 16) || !aligned(Y, 4) || !aligned(Yf, 4) || !aligned(scale, 4) ||
+        !aligned(bias, 4))
+        return FATNN_ERR_ALIGN;
+    GemmParams p{};
+    p.W = reinterpret_cast<const plane2*>(Wp);
+    p.A = reinterpret_cast<const plane2*>(Xp);
+    set_ternary_consts(p, Wp, Cout, cs.K, act_mode);
+    p.K = (int32_t)cs.K;
+    p.M = (int32_t)Cout;
+    p.N = (int32_t)cs.N;
+    p.Kw = (int32_t)(cs.K / 32);
+    p.C = Y; p.ldc_m = 1; p.ldc_n = Cout;
+    p.Cf = Yf; p.ldf_m = 1; p.ldf_n = Cout;
+    p.scale = scale; p.bias = bias;
+    p.is_conv = 1;
+    p.B = (int32_t)B; p.H = (int32_t)H; p.Wd = (int32_t)W; p.Cw = (int32_t)(Cin / 32);
+    p.Ho = (int32_t)cs.Ho; p.Wo = (int32_t)cs.Wo; p.R = R; p.S = S; p.stride = stride; p.pad = pad;
+    // a padded tap is the value 0: level 1 = codec 01 in symmetric mode, level 0 = codec 00 in ReLU mode
+    p.pad_x = 0u;
+    p.pad_y = (act_mode == FATNN_SYM) ? 0xFFFFFFFFu : 0u;
+    return launch_gemm(p, OP_TERNARY, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+}
+
+int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int basis, int32_t* C,
+                      int64_t ldc, void* stream) {
+    int rc = check_gemm_dims(M, N, K);
+    if (rc != FATNN_OK) return rc;
+    if (basis != FATNN_BASIS_TERNARY && basis != FATNN_BASIS_UNIFORM) return FATNN_ERR_UNSUPPORTED;
+    if (basis == FATNN_BASIS_UNIFORM && K > (1 << 20)) return FATNN_ERR_SIZE;   // |C| <= 9K in int32
+    if (M == 0 || N == 0) return FATNN_OK;
+    if (C == nullptr) return FATNN_ERR_NULL;
+    if (ldc < N) return FATNN_ERR_SHAPE;
+    if (Wp == nullptr || Ap == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(Wp, 16) || !aligned(Ap, 16) || !aligned(C, 4)) return FATNN_ERR_ALIGN;
+    GemmParams p{};
+    p.W = reinterpret_cast<const plane2*>(Wp);
+    p.A = reinterpret_cast<const plane2*>(Ap);
+    p.K = (int32_t)K;
+    p.M = (int32_t)M;
+    p.N = (int32_t)N;
+    p.Kw = (int32_t)fatnn_words_per_row(K);
+    p.C = C; p.ldc_m = ldc; p.ldc_n = 1;
+    p.is_conv = 0;
+    const int op = basis == FATNN_BASIS_TERNARY ? OP_TWOBIT_TERNARY : OP_TWOBIT_UNIFORM;
+    return launch_gemm(p, op, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+}
+
+int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                        int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t* Y, void* stream) {
+    ConvShape cs;
+    int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
+    if (rc != FATNN_OK) return rc;
+    if (basis != FATNN_BASIS_TERNARY) return FATNN_ERR_UNSUPPORTED;
+    if (B == 0 || Cout == 0) return FATNN_OK;
+    if (Y == nullptr) return FATNN_ERR_NULL;
+    if (Wp == nullptr || Xp == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(Wp, 16) || !aligned(Xp, 16) || !aligned(Y, 4)) return FATNN_ERR_ALIGN;
+    GemmParams p{};
+    p.W = reinterpret_cast<const plane2*>(Wp);
+    p.A = reinterpret_cast<const plane2*>(Xp);
+    p.K = (int32_t)cs.K;
+    p.M = (int32_t)Cout;
+    p.N = (int32_t)cs.N;
+    p.Kw = (int32_t)(cs.K / 32);
+    p.C = Y; p.ldc_m = 1; p.ldc_n = Cout;
+    p.is_conv = 1;
+    p.B = (int32_t)B; p.H = (int32_t)H; p.Wd = (int32_t)W; p.Cw = (int32_t)(Cin / 32);
+    p.Ho = (int32_t)cs.Ho; p.Wo = (int32_t)cs.Wo; p.R = R; p.S = S; p.stride = stride; p.pad = pad;
+    p.pad_x = 0u;            // code 01: the value 0 of Table 1
+    p.pad_y = 0xFFFFFFFFu;
+    return launch_gemm(p, OP_TWOBIT_TERNARY, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK
+                                                                                         : FATNN_ERR_HIP;
+}
+
+const char* fatnn_status_str(int status) {
+    switch (status) {
+        case FATNN_OK: return "ok";
+        case FATNN_ERR_NULL: return "required pointer is null";
+        case FATNN_ERR_SHAPE: return "invalid or inconsistent dimensions";
+        case FATNN_ERR_LEVEL: return "level outside {0,1,2}";
+        case FATNN_ERR_ALIGN: return "pointer not aligned as required";
+        case FATNN_ERR_SIZE: return "buffer too small or dimension beyond the supported range";
+        case FATNN_ERR_UNSUPPORTED: return "configuration not supported";
+        case FATNN_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int fatnn_version(void) { return 100; }
+
+}  // extern "C"

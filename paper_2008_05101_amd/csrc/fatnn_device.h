@@ -1,0 +1,64 @@
+// Shared declarations of the HIP translation units (kernels + host layer).
+// gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace fatnn {
+
+constexpr int kWave = 64;
+
+// A packed element pair: two 32-bit plane words covering 32 consecutive k.
+using plane2 = uint2;
+
+enum PackKind : int {
+    PACK_ACT = 0,      // .x = (l == 2), .y = (l >= 1)
+    PACK_WEIGHT = 1,   // .x = (l == 2), .y = (l != 1)
+    PACK_TWOBIT = 2    // .x = bit 1,    .y = bit 0 of a code in {0,1,2,3}
+};
+
+// Source addressing of a level tensor: element (row, k) lives at
+//   levels[row_off(row) + k_off(k)]; only the gathering kernel uses the general form.
+struct GatherDesc {
+    // row = (r0 * n1 + r1):   row offset = r0 * rs0 + r1 * rs1
+    int64_t n1, rs0, rs1;
+    // k = (k0 * C + c):       k offset  = k0 * ks0 + c * ks1
+    int64_t C, ks0, ks1;
+};
+
+int launch_pack_contiguous(const int8_t* levels, int64_t rows, int64_t K, int kind, plane2* packed,
+                           int32_t* n_invalid, hipStream_t stream);
+int launch_pack_gather(const int8_t* levels, int64_t rows, int64_t K, GatherDesc g, int kind,
+                       plane2* packed, int32_t* n_invalid, hipStream_t stream);
+int launch_row_constants(const plane2* packed, int64_t rows, int64_t Kw, int32_t* nnz, int32_t* npos,
+                         hipStream_t stream);
+
+enum GemmOp : int {
+    OP_TERNARY = 0,        // Eq. 3 in its reduced form: 2 logic + 2 popcount per word pair
+    OP_TWOBIT_TERNARY = 1, // Eq. 2, alpha = beta = (1/2,1/2): 4 xor + 4 popcount, one accumulator
+    OP_TWOBIT_UNIFORM = 2  // Eq. 2, alpha = beta = (1,2):     4 xor + 4 popcount, three accumulators
+};
+
+struct GemmParams {
+    const plane2* W;        // [M][Kw]
+    const plane2* A;        // GEMM: [N][Kw];  conv: [B][H][Wd][Cw]
+    const int32_t* rowc;    // per-row constant source (nnz or npos), ternary op only
+    int32_t cmul;           // C = cmul * rowc[m] - P'        (ternary)
+    int32_t K;              // true element count (two-bit epilogues)
+    int32_t M, N, Kw;
+    int32_t* C;             // may be null
+    int64_t ldc_m, ldc_n;   // element strides of C along m and n
+    float* Cf;              // may be null
+    int64_t ldf_m, ldf_n;
+    const float* scale;
+    const float* bias;
+    // convolution front end (is_conv != 0)
+    int32_t is_conv;
+    int32_t B, H, Wd, Cw, Ho, Wo, R, S, stride, pad;
+    uint32_t pad_x, pad_y;  // plane words of a padded tap (value 0)
+};
+
+int launch_gemm(const GemmParams& p, int op, hipStream_t stream);
+
+}  // namespace fatnn

@@ -1,0 +1,238 @@
+// Data packing (Algorithm 1, step 1) from level indices into plane words, and the
+// weight-side precomputation that the paper does once after training (end of
+// Section 3.3: the mask comes from the weights and is fixed).
+//
+// One thread turns 32 consecutive levels of one row into one pair of 32-bit words.
+// Neighbouring lanes take neighbouring words of the same row, so a wavefront reads
+// 2 KiB and writes 512 B of contiguous memory: the pass is bound by HBM, not ALU.
+#include "fatnn_device.h"
+
+namespace fatnn {
+namespace {
+
+// Gathers the least significant bit of each of the four bytes of v into a nibble
+// (byte 0 -> bit 0).  The partial products land on distinct bit positions, so no
+// carry can reach bits 24..27.
+__device__ __forceinline__ uint32_t lsb_nibble(uint32_t v) {
+    return ((v & 0x01010101u) * 0x01020408u) >> 24;
+}
+
+// Four levels (one per byte) -> their two plane bits, plus a flag nibble for bytes
+// that are not valid.  TWOBIT: codes 0..3 are valid and the planes are the code's
+// bits.  Otherwise levels 0..2 are valid, planes are (l==2, l>=1).  An invalid byte
+// becomes (0,1): the value 0 of Table 1.
+template <int KIND>
+__device__ __forceinline__ void planes_of_dword(uint32_t d, uint32_t& p1, uint32_t& p0, uint32_t& bad) {
+    uint32_t t = d & 0xFCFCFCFCu;          // any of the six upper bits set?
+    t |= t >> 4;
+    t |= t >> 2;
+    t |= t >> 1;                           // bit 0 of each byte = OR of that byte's bits
+    uint32_t b1 = d >> 1, b0 = d;
+    uint32_t f = t;
+    if (KIND != PACK_TWOBIT) f |= (b1 & b0);  // level 3
+    bad = lsb_nibble(f);
+    uint32_t hi = lsb_nibble(b1);
+    uint32_t lo = (KIND == PACK_TWOBIT) ? lsb_nibble(b0) : lsb_nibble(b1 | b0);
+    p1 = hi & ~bad;
+    p0 = lo | bad;
+}
+
+template <int KIND>
+__device__ __forceinline__ plane2 finish_word(uint32_t p1, uint32_t p0) {
+    plane2 out;
+    out.x = p1;
+    out.y = (KIND == PACK_WEIGHT) ? ~(p1 ^ p0) : p0;   // weights: non-zero bit = (l != 1)
+    return out;
+}
+
+// Byte that stands for "no element here" (k >= K): the value 0 for ternary planes,
+// all-zero bits for two-bit planes (equal tail bits cancel in the xor of Eq. 1).
+template <int KIND>
+__device__ __forceinline__ uint32_t tail_fill() {
+    return (KIND == PACK_TWOBIT) ? 0u : 0x01010101u;
+}
+
+template <int KIND, bool VEC16>
+__global__ __launch_bounds__(256) void pack_contiguous_kernel(const int8_t* __restrict__ levels, int64_t rows,
+                                                              int64_t K, int64_t Kw,
+                                                              plane2* __restrict__ packed,
+                                                              int32_t* __restrict__ n_invalid) {
+    const int64_t total = rows * Kw;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += stride) {
+        const int64_t row = id / Kw;
+        const int64_t kw = id - row * Kw;
+        const int64_t k0 = kw * 32;
+        const int8_t* src = levels + row * K + k0;
+        uint32_t d[8];
+        if (VEC16) {
+            // K is a multiple of 16 and the base is 16-byte aligned: two 128-bit loads.
+            const uint4* s4 = reinterpret_cast<const uint4*>(src);
+            uint4 a = s4[0];
+            uint4 b;
+            if (k0 + 16 < K) {
+                b = s4[1];
+            } else {
+                b.x = b.y = b.z = b.w = tail_fill<KIND>();
+            }
+            d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w;
+            d[4] = b.x; d[5] = b.y; d[6] = b.z; d[7] = b.w;
+        } else {
+            const uint32_t fill = tail_fill<KIND>() & 0xFFu;
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+                uint32_t v = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int64_t k = k0 + w * 4 + b;
+                    uint32_t byte = (k < K) ? (uint32_t)(uint8_t)src[w * 4 + b] : fill;
+                    v |= byte << (8 * b);
+                }
+                d[w] = v;
+            }
+        }
+        uint32_t p1 = 0, p0 = 0, bad = 0;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            uint32_t q1, q0, qb;
+            planes_of_dword<KIND>(d[w], q1, q0, qb);
+            p1 |= q1 << (4 * w);
+            p0 |= q0 << (4 * w);
+            bad |= qb << (4 * w);
+        }
+        packed[id] = finish_word<KIND>(p1, p0);
+        if (bad != 0 && n_invalid != nullptr) atomicAdd(n_invalid, __popc(bad));
+    }
+}
+
+// General (slow) path for tensors whose K axis is not contiguous (OIHW weights,
+// NCHW activations): one thread still makes one word pair, reading byte by byte.
+template <int KIND>
+__global__ __launch_bounds__(256) void pack_gather_kernel(const int8_t* __restrict__ levels, int64_t rows,
+                                                          int64_t K, int64_t Kw, GatherDesc g,
+                                                          plane2* __restrict__ packed,
+                                                          int32_t* __restrict__ n_invalid) {
+    const int64_t total = rows * Kw;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += stride) {
+        const int64_t row = id / Kw;
+        const int64_t kw = id - row * Kw;
+        const int64_t r0 = row / g.n1, r1 = row - r0 * g.n1;
+        const int8_t* src = levels + r0 * g.rs0 + r1 * g.rs1;
+        const uint32_t fill = tail_fill<KIND>() & 0xFFu;
+        uint32_t p1 = 0, p0 = 0, bad = 0;
+        for (int w = 0; w < 8; ++w) {
+            uint32_t v = 0;
+            for (int b = 0; b < 4; ++b) {
+                const int64_t k = kw * 32 + w * 4 + b;
+                uint32_t byte = fill;
+                if (k < K) {
+                    const int64_t kk0 = k / g.C, c = k - kk0 * g.C;
+                    byte = (uint32_t)(uint8_t)src[kk0 * g.ks0 + c * g.ks1];
+                }
+                v |= byte << (8 * b);
+            }
+            uint32_t q1, q0, qb;
+            planes_of_dword<KIND>(v, q1, q0, qb);
+            p1 |= q1 << (4 * w);
+            p0 |= q0 << (4 * w);
+            bad |= qb << (4 * w);
+        }
+        packed[id] = finish_word<KIND>(p1, p0);
+        if (bad != 0 && n_invalid != nullptr) atomicAdd(n_invalid, __popc(bad));
+    }
+}
+
+// Per weight row: number of non-zero weights and number of +1 weights.  They give
+// Eq. 3's "- N" in the reduced form (N counts only the non-zero weights once the
+// forced-zero fields are dropped) and, in ReLU mode, the added copy of the weights.
+__global__ __launch_bounds__(64) void row_constants_kernel(const plane2* __restrict__ packed, int64_t rows,
+                                                           int64_t Kw, int32_t* __restrict__ nnz,
+                                                           int32_t* __restrict__ npos) {
+    const int64_t row = blockIdx.x;
+    if (row >= rows) return;
+    const plane2* p = packed + row * Kw;
+    int cnt_nz = 0, cnt_pos = 0;
+    for (int64_t kw = threadIdx.x; kw < Kw; kw += kWave) {
+        plane2 w = p[kw];
+        cnt_nz += __popc(w.y);
+        cnt_pos += __popc(w.x & w.y);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        cnt_nz += __shfl_down(cnt_nz, off, kWave);
+        cnt_pos += __shfl_down(cnt_pos, off, kWave);
+    }
+    if (threadIdx.x == 0) {
+        nnz[row] = cnt_nz;
+        npos[row] = cnt_pos;
+    }
+}
+
+int grid_for(int64_t total, int block) {
+    int64_t g = (total + block - 1) / block;
+    const int64_t cap = 256 * 64;  // enough resident work for 256 CUs; the kernels stride
+    if (g > cap) g = cap;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+}  // namespace
+
+int launch_pack_contiguous(const int8_t* levels, int64_t rows, int64_t K, int kind, plane2* packed,
+                           int32_t* n_invalid, hipStream_t stream) {
+    const int64_t Kw = (K + 31) / 32;
+    const int64_t total = rows * Kw;
+    if (total == 0) return 0;
+    const bool vec = (K % 16 == 0) && ((reinterpret_cast<uintptr_t>(levels) & 15u) == 0);
+    dim3 grid(grid_for(total, 256)), block(256);
+#define FATNN_LAUNCH_PACK(KIND)                                                                              \
+    if (vec)                                                                                                 \
+        hipLaunchKernelGGL((pack_contiguous_kernel<KIND, true>), grid, block, 0, stream, levels, rows, K, Kw, \
+                           packed, n_invalid);                                                               \
+    else                                                                                                     \
+        hipLaunchKernelGGL((pack_contiguous_kernel<KIND, false>), grid, block, 0, stream, levels, rows, K,   \
+                           Kw, packed, n_invalid);
+    switch (kind) {
+        case PACK_ACT: FATNN_LAUNCH_PACK(PACK_ACT) break;
+        case PACK_WEIGHT: FATNN_LAUNCH_PACK(PACK_WEIGHT) break;
+        case PACK_TWOBIT: FATNN_LAUNCH_PACK(PACK_TWOBIT) break;
+        default: return -1;
+    }
+#undef FATNN_LAUNCH_PACK
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_pack_gather(const int8_t* levels, int64_t rows, int64_t K, GatherDesc g, int kind, plane2* packed,
+                       int32_t* n_invalid, hipStream_t stream) {
+    const int64_t Kw = (K + 31) / 32;
+    const int64_t total = rows * Kw;
+    if (total == 0) return 0;
+    dim3 grid(grid_for(total, 256)), block(256);
+    switch (kind) {
+        case PACK_ACT:
+            hipLaunchKernelGGL((pack_gather_kernel<PACK_ACT>), grid, block, 0, stream, levels, rows, K, Kw, g,
+                               packed, n_invalid);
+            break;
+        case PACK_WEIGHT:
+            hipLaunchKernelGGL((pack_gather_kernel<PACK_WEIGHT>), grid, block, 0, stream, levels, rows, K, Kw,
+                               g, packed, n_invalid);
+            break;
+        case PACK_TWOBIT:
+            hipLaunchKernelGGL((pack_gather_kernel<PACK_TWOBIT>), grid, block, 0, stream, levels, rows, K, Kw,
+                               g, packed, n_invalid);
+            break;
+        default: return -1;
+    }
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_row_constants(const plane2* packed, int64_t rows, int64_t Kw, int32_t* nnz, int32_t* npos,
+                         hipStream_t stream) {
+    if (rows == 0) return 0;
+    hipLaunchKernelGGL(row_constants_kernel, dim3((unsigned)rows), dim3(kWave), 0, stream, packed, rows, Kw,
+                       nnz, npos);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+}  // namespace fatnn

@@ -1,0 +1,346 @@
+// Bit-plane GEMM / implicit-GEMM convolution kernels for gfx950.
+//
+// Ternary operator (Section 3.3).  With the activation codec bits x_hi, x_lo
+// (Table 1, zero spelled 01), the weight sign bit s = (w == +1) and the weight
+// non-zero bit nm = (w != 0) = complement of Eq. 6's mask, Eq. 7 splits into two
+// bit-disjoint parts, mask & auxi and ~mask & xnor, so
+//     popcount(TM) = #zero weights + 2 * #non-zero weights - P',
+//     P' = popcount((x_hi ^ s) & nm) + popcount((x_lo ^ s) & nm),
+// and Eq. 3 becomes  x . w = #non-zero weights - P'.  Everything that depends only
+// on the weights is precomputed per row; the hot loop is one three-input logic
+// operation (v_bitop3_b32) and one accumulating popcount (v_bcnt_u32_b32) per
+// plane word: 2 + 2 VALU instructions per 32 elements.
+//
+// Two-bit operators (Eq. 2 with two planes per operand, Eq. 1 per plane pair):
+// four xor and four popcounts per 32 elements, same tiling, for comparison.
+//
+// Tiling.  A workgroup of WM x WN wavefronts owns a (WM*8*TM) x (WN*8*TN) tile of
+// the output.  A wavefront is an 8 x 8 grid of lanes, each lane holds TM x TN int32
+// accumulators.  K is walked in steps of KT = 8 word pairs (256 elements): the
+// packed tiles of both operands are staged global -> registers -> LDS (double
+// buffered, one barrier per step) in [k-word][row] order, so that a lane's rows
+// for one k-word are fetched with 128-bit LDS reads that are contiguous across the
+// eight lanes of a group.
+#include "fatnn_device.h"
+
+namespace fatnn {
+namespace {
+
+constexpr int KT = 8;        // k-words per LDS stage
+constexpr int LDS_PAD = 4;   // plane2 elements of padding per k-word line (keeps 16 B alignment)
+
+// acc += popcount(x) as the single instruction v_bcnt_u32_b32 (its second source is an
+// addend).  Written as asm because the compiler otherwise re-associates a chain of
+// such additions into popcounts with a zero addend plus a three-input add.
+__device__ __forceinline__ void popc_acc(int32_t& acc, uint32_t x) {
+    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
+}
+
+template <int OP>
+struct Acc;
+
+template <>
+struct Acc<OP_TERNARY> {
+    int32_t v;
+    __device__ __forceinline__ void clear() { v = 0; }
+    __device__ __forceinline__ void step(plane2 w, plane2 a) {
+        popc_acc(v, (a.x ^ w.x) & w.y);
+        popc_acc(v, (a.y ^ w.x) & w.y);
+    }
+};
+
+template <>
+struct Acc<OP_TWOBIT_TERNARY> {
+    int32_t v;
+    __device__ __forceinline__ void clear() { v = 0; }
+    __device__ __forceinline__ void step(plane2 w, plane2 a) {
+        popc_acc(v, a.x ^ w.x);
+        popc_acc(v, a.x ^ w.y);
+        popc_acc(v, a.y ^ w.x);
+        popc_acc(v, a.y ^ w.y);
+    }
+};
+
+template <>
+struct Acc<OP_TWOBIT_UNIFORM> {
+    int32_t s00, s01, s11;   // by weight of the plane pair: 1, 2, 4
+    __device__ __forceinline__ void clear() { s00 = s01 = s11 = 0; }
+    __device__ __forceinline__ void step(plane2 w, plane2 a) {
+        popc_acc(s00, a.y ^ w.y);
+        popc_acc(s01, a.x ^ w.y);
+        popc_acc(s01, a.y ^ w.x);
+        popc_acc(s11, a.x ^ w.x);
+    }
+};
+
+template <int OP>
+__device__ __forceinline__ int32_t finalize(const Acc<OP>& acc, const GemmParams& p, int32_t rowconst);
+
+template <>
+__device__ __forceinline__ int32_t finalize<OP_TERNARY>(const Acc<OP_TERNARY>& acc, const GemmParams&,
+                                                        int32_t rowconst) {
+    return rowconst - acc.v;
+}
+template <>
+__device__ __forceinline__ int32_t finalize<OP_TWOBIT_TERNARY>(const Acc<OP_TWOBIT_TERNARY>& acc,
+                                                               const GemmParams& p, int32_t) {
+    // sum_mk (1/4) * (K - 2 * popcount(x_m ^ y_k))
+    return p.K - (acc.v >> 1);
+}
+template <>
+__device__ __forceinline__ int32_t finalize<OP_TWOBIT_UNIFORM>(const Acc<OP_TWOBIT_UNIFORM>& acc,
+                                                               const GemmParams& p, int32_t) {
+    // sum_mk 2^(m+k) * (K - 2 * popcount(x_m ^ y_k))
+    return 9 * p.K - 2 * acc.s00 - 4 * acc.s01 - 8 * acc.s11;
+}
+
+template <int OP, int WM, int WN, int TM, int TN, bool CONV>
+__global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
+                                                                   const int ntiles) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr int BM = WM * 8 * TM;
+    constexpr int BN = WN * 8 * TN;
+    constexpr int LW = (BM * KT) / NT;   // staged word pairs per thread, weights
+    constexpr int LA = (BN * KT) / NT;   // ... activations
+    static_assert((BM * KT) % NT == 0 && (BN * KT) % NT == 0, "tile does not divide over the threads");
+    static_assert(TM % 2 == 0 && TN % 2 == 0, "lanes own row pairs");
+    static_assert(NT % KT == 0, "a thread keeps one k-word slot");
+    constexpr int ROWS_PER_PASS = NT / KT;
+    constexpr int PW = BM + LDS_PAD;
+    constexpr int PA = BN + LDS_PAD;
+
+    __shared__ __attribute__((aligned(16))) plane2 Ws[2][KT][PW];
+    __shared__ __attribute__((aligned(16))) plane2 As[2][KT][PA];
+
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
+    // tiles so that the tiles sharing an activation panel meet in one L2.
+    const int per_xcd = gridDim.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= ntiles) return;
+    const int tile_m = logical % tiles_m;
+    const int tile_n = logical / tiles_m;
+    const int row0 = tile_m * BM;
+    const int col0 = tile_n * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wave_m = wave % WM;
+    const int wave_n = wave / WM;
+    const int ly = lane >> 3;
+    const int lx = lane & 7;
+
+    const int ld_j = tid % KT;
+    const int ld_r = tid / KT;
+
+    // ---- global addressing of the staged loads ------------------------------------------
+    // Both operands are read through buffer resources: a load whose byte offset is at or
+    // beyond num_records returns zero, which takes care of rows past M / N without any
+    // branch; k-words past the end of a row are sent to kOutOfRange on purpose.
+    constexpr uint32_t kOutOfRange = 0x80000000u;
+    constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
+    const int64_t wbase = (int64_t)row0 * p.Kw;
+    const int64_t wleft = ((int64_t)p.M * p.Kw - wbase) * (int64_t)sizeof(plane2);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<plane2*>(p.W + wbase), 0, (int)(wleft < 0x7FFFFFFFLL ? wleft : 0x7FFFFFFFLL), kRsrcFlags);
+    uint32_t woff[LW];
+#pragma unroll
+    for (int i = 0; i < LW; ++i) woff[i] = (uint32_t)(ld_r + i * ROWS_PER_PASS) * (uint32_t)p.Kw * 8u;
+
+    int64_t abase, aleft;
+    uint32_t aoff[LA];   // GEMM: byte offset of the row.  conv: byte offset of the column's image
+    int hi0[LA], wi0[LA];
+    if (CONV) {
+        const int64_t img = (int64_t)p.H * p.Wd * p.Cw;          // word pairs per image
+        const int b0 = col0 / (p.Ho * p.Wo);
+        abase = (int64_t)b0 * img;
+        aleft = ((int64_t)p.B * img - abase) * (int64_t)sizeof(plane2);
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int n = col0 + ld_r + i * ROWS_PER_PASS;
+            const int nn = n < p.N ? n : col0;   // columns past N are never stored; keep them in range
+            const int wo = nn % p.Wo;
+            const int t = nn / p.Wo;
+            const int ho = t % p.Ho;
+            const int b = t / p.Ho;
+            hi0[i] = ho * p.stride - p.pad;
+            wi0[i] = wo * p.stride - p.pad;
+            aoff[i] = (uint32_t)(b - b0) * (uint32_t)img * 8u;
+        }
+    } else {
+        abase = (int64_t)col0 * p.Kw;
+        aleft = ((int64_t)p.N * p.Kw - abase) * (int64_t)sizeof(plane2);
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            hi0[i] = wi0[i] = 0;
+            aoff[i] = (uint32_t)(ld_r + i * ROWS_PER_PASS) * (uint32_t)p.Kw * 8u;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<plane2*>(p.A + abase), 0, (int)(aleft < 0x7FFFFFFFLL ? aleft : 0x7FFFFFFFLL), kRsrcFlags);
+
+    auto load2 = [](const __amdgpu_buffer_rsrc_t& r, uint32_t off) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+        plane2 o;
+        o.x = v[0];
+        o.y = v[1];
+        return o;
+    };
+
+    plane2 wreg[LW], areg[LA];
+    auto fetch = [&](int kt) {
+        const int kw = kt * KT + ld_j;
+        const bool kok = kw < p.Kw;
+#pragma unroll
+        for (int i = 0; i < LW; ++i) wreg[i] = load2(wrsrc, kok ? woff[i] + (uint32_t)kw * 8u : kOutOfRange);
+        if (CONV) {
+            // k-word -> (filter tap, channel word); c is innermost in K
+            const int kwc = kok ? kw : 0;
+            const int tap = kwc / p.Cw;
+            const int cw = kwc - tap * p.Cw;
+            const int r = tap / p.S;
+            const int s = tap - r * p.S;
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const int hi = hi0[i] + r;
+                const int wi = wi0[i] + s;
+                const bool inside = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd;
+                const uint32_t off = aoff[i] + (uint32_t)((hi * p.Wd + wi) * p.Cw + cw) * 8u;
+                plane2 v = load2(arsrc, (kok && inside) ? off : kOutOfRange);
+                // a padded tap is the value 0; only its low plane can be non-zero (codec 01)
+                v.y |= (kok && !inside) ? p.pad_y : 0u;
+                areg[i] = v;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LA; ++i) areg[i] = load2(arsrc, kok ? aoff[i] + (uint32_t)kw * 8u : kOutOfRange);
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LW; ++i) Ws[buf][ld_j][ld_r + i * ROWS_PER_PASS] = wreg[i];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) As[buf][ld_j][ld_r + i * ROWS_PER_PASS] = areg[i];
+    };
+
+    Acc<OP> acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int c = 0; c < TN; ++c) acc[i][c].clear();
+
+    // Lane-owned rows/columns inside the wavefront tile: pairs at a stride of 16, so
+    // that one 128-bit LDS read is contiguous over the eight lane groups.
+    const int wrow = wave_m * 8 * TM + ly * 2;
+    const int wcol = wave_n * 8 * TN + lx * 2;
+
+    auto read_frag = [&](int buf, int j, plane2 (&w)[TM], plane2 (&a)[TN]) {
+#pragma unroll
+        for (int q = 0; q < TM / 2; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4*>(&Ws[buf][j][wrow + q * 16]);
+            w[2 * q].x = v.x; w[2 * q].y = v.y;
+            w[2 * q + 1].x = v.z; w[2 * q + 1].y = v.w;
+        }
+#pragma unroll
+        for (int q = 0; q < TN / 2; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4*>(&As[buf][j][wcol + q * 16]);
+            a[2 * q].x = v.x; a[2 * q].y = v.y;
+            a[2 * q + 1].x = v.z; a[2 * q + 1].y = v.w;
+        }
+    };
+
+    const int nkt = (p.Kw + KT - 1) / KT;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nkt) fetch(kt + 1);
+        // Fragments of k-word j+1 are read from LDS while k-word j is consumed.  The
+        // scheduling fences keep the compiler from hoisting every LDS read of the stage
+        // to its top (which needs more registers than there are).
+        plane2 w[2][TM], a[2][TN];
+        read_frag(buf, 0, w[0], a[0]);
+#pragma unroll
+        for (int j = 0; j < KT; ++j) {
+            if (j + 1 < KT) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (kt + 1 < nkt) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: Eq. 3's subtraction, then the optional fp32 scale -----------------------
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = row0 + wrow + (i >> 1) * 16 + (i & 1);
+        if (m >= p.M) continue;
+        int32_t rc = 0;
+        if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
+        float sc = 0.f, bs = 0.f;
+        if (p.Cf != nullptr) {
+            sc = p.scale[m];
+            if (p.bias != nullptr) bs = p.bias[m];
+        }
+#pragma unroll
+        for (int c = 0; c < TN; ++c) {
+            const int n = col0 + wcol + (c >> 1) * 16 + (c & 1);
+            if (n >= p.N) continue;
+            const int32_t v = finalize<OP>(acc[i][c], p, rc);
+            if (p.C != nullptr) p.C[(int64_t)m * p.ldc_m + (int64_t)n * p.ldc_n] = v;
+            if (p.Cf != nullptr) {
+                float f = __fmul_rn(sc, (float)v);
+                if (p.bias != nullptr) f = __fadd_rn(f, bs);
+                p.Cf[(int64_t)m * p.ldf_m + (int64_t)n * p.ldf_n] = f;
+            }
+        }
+    }
+}
+
+template <int OP, int WM, int WN, int TM, int TN>
+int launch_shape(const GemmParams& p, hipStream_t stream) {
+    constexpr int BM = WM * 8 * TM;
+    constexpr int BN = WN * 8 * TN;
+    const int tiles_m = (p.M + BM - 1) / BM;
+    const int64_t tiles_n = ((int64_t)p.N + BN - 1) / BN;
+    const int64_t ntiles = (int64_t)tiles_m * tiles_n;
+    if (ntiles > 0x7FFFFFF0LL) return -2;
+    const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
+    if (p.is_conv)
+        hipLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true>), dim3(grid), dim3(64 * WM * WN), 0,
+                           stream, p, tiles_m, (int)ntiles);
+    else
+        hipLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false>), dim3(grid), dim3(64 * WM * WN), 0,
+                           stream, p, tiles_m, (int)ntiles);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Picks the workgroup shape: large square-ish tiles when there is enough work to fill
+// 256 CUs several times over, a tall-skinny tile when M is one wavefront tall, and
+// single-wavefront tiles for small problems.
+template <int OP, int TM, int TN>
+int launch_op(const GemmParams& p, hipStream_t stream) {
+    constexpr int WTM = 8 * TM, WTN = 8 * TN;
+    const int64_t wave_tiles = (((int64_t)p.M + WTM - 1) / WTM) * (((int64_t)p.N + WTN - 1) / WTN);
+    if (wave_tiles < 4 * 1024) return launch_shape<OP, 1, 1, TM, TN>(p, stream);
+    if (p.M <= WTM) return launch_shape<OP, 1, 4, TM, TN>(p, stream);
+    return launch_shape<OP, 2, 2, TM, TN>(p, stream);
+}
+
+}  // namespace
+
+int launch_gemm(const GemmParams& p, int op, hipStream_t stream) {
+    if (p.M == 0 || p.N == 0) return 0;
+    switch (op) {
+        case OP_TERNARY: return launch_op<OP_TERNARY, 8, 8>(p, stream);
+        case OP_TWOBIT_TERNARY: return launch_op<OP_TWOBIT_TERNARY, 8, 8>(p, stream);
+        case OP_TWOBIT_UNIFORM: return launch_op<OP_TWOBIT_UNIFORM, 8, 4>(p, stream);
+        default: return -3;
+    }
+}
+
+}  // namespace fatnn

@@ -1,0 +1,333 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, bit-exact in
+int32; the fp32 scale epilogue within 1e-6 relative (bit-equal is expected: both
+sides do one correctly rounded multiply and one add)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+fatnn = pytest.importorskip("paper_2008_05101_amd")
+
+DEV = "cuda:0"
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+# ----------------------------------------------------------------------------- host-side decode (test only)
+def decode_packed(buf: torch.Tensor, rows: int, K: int, role: int):
+    """Packed plane words -> level indices, on the host.  Weights: (s, nm) planes."""
+    Kw = (K + 31) // 32
+    words = buf.cpu().numpy()[: rows * Kw * 8].view(np.uint32).reshape(rows, Kw, 2)
+    bits = np.unpackbits(words.view(np.uint8).reshape(rows, Kw, 2, 4), axis=-1, bitorder="little")
+    bits = bits.reshape(rows, Kw, 2, 32)
+    px = bits[:, :, 0, :].reshape(rows, Kw * 32)
+    py = bits[:, :, 1, :].reshape(rows, Kw * 32)
+    if role == fatnn.ACT:
+        lv = px.astype(np.int8) + py.astype(np.int8)           # hi + lo = popcount of the codec
+        assert not np.any((px == 1) & (py == 0)), "activations must spell zero as 01"
+    else:
+        lv = np.where(py == 0, 1, np.where(px == 1, 2, 0)).astype(np.int8)
+    return lv[:, :K], lv[:, K:]
+
+
+def gemm_gpu(Lw, La, mode, **kw):
+    M, K = Lw.shape
+    N = La.shape[0]
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    return fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, **kw)
+
+
+def conv_gpu(Lw, Lx, stride, pad, mode, **kw):
+    Cout, R, S, Cin = Lw.shape
+    B, H, W, _ = Lx.shape
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT, fatnn.OHWI)
+    Xp = fatnn.pack_ternary(dev(Lx), fatnn.ACT, fatnn.NHWC)
+    return fatnn.ternary_conv2d(Wp, Xp, B, Cin, H, W, Cout, R, S, stride, pad, mode, **kw)
+
+
+# ----------------------------------------------------------------------------- packing
+@pytest.mark.parametrize("K", [1, 5, 31, 32, 33, 48, 64, 100, 576, 4609])
+@pytest.mark.parametrize("role", [0, 1])
+def test_pack_roundtrip(K, role):
+    rnd = np.random.default_rng(K * 2 + role)
+    rows = 37
+    L = rnd.integers(0, 3, size=(rows, K), dtype=np.int8)
+    cnt = torch.zeros(1, dtype=torch.int32, device=DEV)
+    buf = fatnn.pack_ternary(dev(L), role, n_invalid=cnt)
+    torch.cuda.synchronize()
+    body, tail = decode_packed(buf, rows, K, role)
+    assert np.array_equal(body, L)
+    assert (tail == 1).all()            # tail slots hold the value 0
+    assert int(cnt.item()) == 0
+    if role == fatnn.WEIGHT:
+        off = fatnn.weight_consts_offset(rows, K)
+        consts = buf.cpu().numpy()[off: off + rows * 8].view(np.int32)
+        assert np.array_equal(consts[:rows], (L != 1).sum(axis=1))
+        assert np.array_equal(consts[rows:], (L == 2).sum(axis=1))
+
+
+def test_pack_counts_invalid_levels_and_packs_them_as_zero():
+    rnd = np.random.default_rng(9)
+    L = rnd.integers(0, 3, size=(16, 96), dtype=np.int8)
+    bad = [(0, 0, 3), (3, 17, -1), (7, 95, 77), (15, 40, -128), (15, 41, 4)]
+    Lb = L.copy()
+    for r, k, v in bad:
+        Lb[r, k] = v
+        L[r, k] = 1
+    for role in (0, 1):
+        cnt = torch.zeros(1, dtype=torch.int32, device=DEV)
+        buf = fatnn.pack_ternary(dev(Lb), role, n_invalid=cnt)
+        torch.cuda.synchronize()
+        assert int(cnt.item()) == len(bad)
+        body, _ = decode_packed(buf, 16, 96, role)
+        assert np.array_equal(body, L)
+
+
+def test_pack_layouts_agree():
+    rnd = np.random.default_rng(10)
+    w = rnd.integers(0, 3, size=(6, 3, 3, 64), dtype=np.int8)          # OHWI
+    a = fatnn.pack_ternary(dev(w), fatnn.WEIGHT, fatnn.OHWI)
+    b = fatnn.pack_ternary(dev(np.ascontiguousarray(w.transpose(0, 3, 1, 2))), fatnn.WEIGHT, fatnn.OIHW)
+    nwords = 6 * (9 * 64 // 32) * 8                      # the alignment gap before the constants is not written
+    off = fatnn.weight_consts_offset(6, 9 * 64)
+    assert torch.equal(a[:nwords], b[:nwords])
+    assert torch.equal(a[off:off + 6 * 8], b[off:off + 6 * 8])
+    x = rnd.integers(0, 3, size=(2, 5, 7, 32), dtype=np.int8)          # NHWC
+    a = fatnn.pack_ternary(dev(x), fatnn.ACT, fatnn.NHWC)
+    b = fatnn.pack_ternary(dev(np.ascontiguousarray(x.transpose(0, 3, 1, 2))), fatnn.ACT, fatnn.NCHW)
+    assert torch.equal(a, b)
+    c = fatnn.pack_ternary(dev(x.reshape(-1, 32)), fatnn.ACT, fatnn.ROWMAJOR_K)
+    assert torch.equal(a, c)
+
+
+# ----------------------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("M,N,K", [
+    (1, 1, 1), (3, 5, 31), (64, 64, 32), (65, 63, 33), (7, 200, 65), (130, 70, 257),
+    (128, 128, 256), (129, 257, 300), (200, 1000, 1000), (64, 1500, 96),
+])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_gemm_parity_small_and_ragged(M, N, K, mode):
+    rnd = np.random.default_rng(M * 7 + N * 3 + K + mode)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    C, _ = gemm_gpu(Lw, La, mode)
+    assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, mode))
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_gemm_cfg1(mode):
+    case = si.cfg1()
+    Lw, La = case.make()
+    C, _ = gemm_gpu(Lw, La, mode)
+    assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, mode))
+
+
+def test_gemm_degenerate_operands():
+    K = 777
+    for lw, la, mode, want in [(2, 2, 0, K), (2, 0, 0, -K), (1, 2, 0, 0), (2, 1, 0, 0), (2, 2, 1, 2 * K),
+                               (0, 2, 1, -2 * K), (2, 0, 1, 0)]:
+        Lw = np.full((70, K), lw, np.int8)
+        La = np.full((66, K), la, np.int8)
+        C, _ = gemm_gpu(Lw, La, mode)
+        assert (C.cpu().numpy() == want).all()
+
+
+def test_gemm_accepts_the_other_spelling_of_zero():
+    # Table 1 allows 10 as well as 01 for the value 0: hand-pack activations with 10.
+    rnd = np.random.default_rng(12)
+    M, N, K = 33, 40, 96
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    words = Ap.cpu().numpy().view(np.uint32).reshape(N, K // 32, 2).copy()
+    hi, lo = words[:, :, 0], words[:, :, 1]
+    zero = ~hi & lo
+    flip = zero & np.uint32(0xA5A5F00F)          # respell some zeros as 10
+    words[:, :, 0] = hi | flip
+    words[:, :, 1] = lo & ~flip
+    Ap2 = torch.from_numpy(words.view(np.uint8).reshape(-1)).to(DEV)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    C, _ = fatnn.ternary_gemm(Wp, Ap2, M, N, K, fatnn.SYM)
+    assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
+
+
+def test_gemm_empty_and_strided_output():
+    Lw = np.ones((4, 40), np.int8)
+    La = np.ones((0, 40), np.int8)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = torch.empty(16, dtype=torch.uint8, device=DEV)
+    C, _ = fatnn.ternary_gemm(Wp, Ap, 4, 0, 40)
+    assert C.shape == (4, 0)
+    rnd = np.random.default_rng(1)
+    Lw = rnd.integers(0, 3, size=(10, 70), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(20, 70), dtype=np.int8)
+    big = torch.full((10, 32), -7, dtype=torch.int32, device=DEV)
+    out = big[:, :20]
+    gemm_gpu(Lw, La, 0, out=out)
+    assert np.array_equal(out.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
+    assert (big[:, 20:] == -7).all()
+
+
+def test_gemm_scale_epilogue():
+    rnd = np.random.default_rng(14)
+    M, N, K = 70, 90, 500
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    scale = si.scale_vec(rnd, M)
+    bias = si.bias_vec(rnd, M)
+    C = oracle.ternary_gemm(Lw, La, 1)
+    for b in (None, bias):
+        Ci, Cf = gemm_gpu(Lw, La, 1, scale=dev(scale), bias=None if b is None else dev(b))
+        assert np.array_equal(Ci.cpu().numpy(), C)
+        want = oracle.scale_epilogue(C, scale, b, channel_is_row=True)
+        got = Cf.cpu().numpy()
+        np.testing.assert_allclose(got, want, rtol=1e-6, atol=0)
+        assert np.array_equal(got, want)
+    # fp32 only (no int32 output)
+    Ci, Cf = gemm_gpu(Lw, La, 1, scale=dev(scale), want_int=False)
+    assert Ci is None
+    assert np.array_equal(Cf.cpu().numpy(), oracle.scale_epilogue(C, scale, None, True))
+
+
+# ----------------------------------------------------------------------------- convolution
+@pytest.mark.parametrize("Cin,Cout,H,W,R,stride,pad", [
+    (32, 5, 6, 7, 3, 1, 1), (64, 64, 9, 9, 3, 1, 1), (64, 70, 12, 10, 3, 2, 1), (96, 33, 8, 8, 3, 1, 1),
+    (64, 128, 14, 14, 1, 2, 0), (256, 64, 7, 9, 1, 1, 0), (32, 16, 5, 5, 3, 1, 0), (128, 130, 7, 7, 3, 1, 1),
+])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_conv_parity_small(Cin, Cout, H, W, R, stride, pad, mode):
+    rnd = np.random.default_rng(Cin + Cout + H + R + stride + mode)
+    B = 3
+    Lw = rnd.integers(0, 3, size=(Cout, R, R, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(B, H, W, Cin), dtype=np.int8)
+    Y, _ = conv_gpu(Lw, Lx, stride, pad, mode)
+    assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, mode))
+
+
+def test_conv_cfg2_full_with_scale_epilogue():
+    case = si.cfg2()
+    Lw, Lx = case.make()
+    scale, bias = case.make_scale_bias()
+    Y, Yf = conv_gpu(Lw, Lx, 1, 1, case.act_mode, scale=dev(scale), bias=dev(bias))
+    want = oracle.ternary_conv2d(Lw, Lx, 1, 1, case.act_mode)
+    assert np.array_equal(Y.cpu().numpy(), want)
+    wantf = oracle.scale_epilogue(want, scale, bias, channel_is_row=False)
+    np.testing.assert_allclose(Yf.cpu().numpy(), wantf, rtol=1e-6, atol=0)
+    assert np.array_equal(Yf.cpu().numpy(), wantf)
+    Ys, _ = conv_gpu(Lw, Lx, 1, 1, fatnn.SYM)
+    assert np.array_equal(Ys.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, 1, 1, 0))
+
+
+@pytest.mark.parametrize("layer", range(19))
+def test_conv_cfg3_layers_batch4(layer):
+    case = si.cfg3(batch=4)[layer]
+    Lw, Lx = case.make()
+    Y, _ = conv_gpu(Lw, Lx, case.stride, case.pad, case.act_mode)
+    assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode))
+
+
+def test_conv_cfg3_full_batch_sampled_images():
+    # full launch configuration (batch 64); the oracle recomputes four whole images of three layers
+    for layer in (0, 9, 15):
+        case = si.cfg3(batch=64)[layer]
+        Lw, Lx = case.make()
+        Y, _ = conv_gpu(Lw, Lx, case.stride, case.pad, case.act_mode)
+        Y = Y.cpu().numpy()
+        for b in (0, 21, 42, 63):
+            want = oracle.ternary_conv2d(Lw, Lx[b:b + 1], case.stride, case.pad, case.act_mode)
+            assert np.array_equal(Y[b:b + 1], want), (layer, b)
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_conv_cfg5_bottleneck_1x1_full(idx):
+    case = si.cfg5_bottleneck()[idx]
+    Lw, Lx = case.make()
+    Y, _ = conv_gpu(Lw, Lx, 1, 0, case.act_mode)
+    Y = Y.cpu().numpy()
+    for b in (0, 63, 127):
+        want = oracle.ternary_conv2d(Lw, Lx[b:b + 1], 1, 0, case.act_mode)
+        assert np.array_equal(Y[b:b + 1], want)
+    # a 1x1 convolution is the GEMM over pixels
+    C, _ = gemm_gpu(Lw.reshape(case.Cout, case.Cin), Lx[:2].reshape(-1, case.Cin), case.act_mode)
+    assert np.array_equal(C.cpu().numpy().T, Y[:2].reshape(-1, case.Cout))
+
+
+# ----------------------------------------------------------------------------- the large and the ragged GEMMs
+def test_gemm_cfg5_ragged_k4609_full():
+    case = si.cfg5_ragged()
+    Lw, La = case.make()
+    C, _ = gemm_gpu(Lw, La, 0)
+    assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
+
+
+def test_gemv_cfg5_full():
+    case = si.cfg5_gemv()
+    Lw, La = case.make()
+    for mode in (0, 1):
+        C, _ = gemm_gpu(Lw, La, mode)
+        assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, mode))
+
+
+def test_gemm_cfg4_full_size_sampled_rows_and_columns():
+    case = si.cfg4()
+    Lw, La = case.make()
+    C, _ = gemm_gpu(Lw, La, 0)
+    C = C.cpu().numpy()
+    rnd = np.random.default_rng(44)
+    rows = np.sort(rnd.choice(case.M, 48, replace=False))
+    rows[0], rows[-1] = 0, case.M - 1
+    assert np.array_equal(C[rows], oracle.ternary_gemm(Lw[rows], La, 0))
+    cols = np.sort(rnd.choice(case.N, 48, replace=False))
+    cols[0], cols[-1] = 0, case.N - 1
+    assert np.array_equal(C[:, cols], oracle.ternary_gemm(Lw, La[cols], 0))
+    # properties that hold at any size: parity of C and the magnitude bound
+    nzw = torch.from_numpy((Lw != 1).astype(np.float32)).to(DEV)
+    nza = torch.from_numpy((La != 1).astype(np.float32)).to(DEV)
+    both = (nzw @ nza.T).to(torch.int32)                  # exact in fp32: counts <= 8192
+    Cd = torch.from_numpy(C).to(DEV)
+    assert bool(((Cd & 1) == (both & 1)).all())
+    assert bool((Cd.abs() <= both).all())
+
+
+# ----------------------------------------------------------------------------- conventional two-bit path
+@pytest.mark.parametrize("M,N,K", [(3, 5, 31), (65, 63, 33), (130, 70, 257), (200, 300, 1000)])
+@pytest.mark.parametrize("basis", [0, 1])
+def test_twobit_gemm_parity(M, N, K, basis):
+    rnd = np.random.default_rng(M + N + K + basis)
+    Qw = rnd.integers(0, 4, size=(M, K), dtype=np.int8)
+    Qa = rnd.integers(0, 4, size=(N, K), dtype=np.int8)
+    Wp = fatnn.pack_twobit(dev(Qw))
+    Ap = fatnn.pack_twobit(dev(Qa))
+    C = fatnn.twobit_gemm(Wp, Ap, M, N, K, basis)
+    assert np.array_equal(C.cpu().numpy(), oracle.twobit_gemm(Qw, Qa, basis))
+
+
+def test_twobit_on_ternary_data_equals_ternary_path():
+    case = si.cfg1()
+    Lw, La = case.make()
+    code = np.array([0, 1, 3], dtype=np.int8)
+    Wp = fatnn.pack_twobit(dev(code[Lw]))
+    Ap = fatnn.pack_twobit(dev(code[La]))
+    C2 = fatnn.twobit_gemm(Wp, Ap, case.M, case.N, case.K, fatnn.BASIS_TERNARY)
+    C3, _ = gemm_gpu(Lw, La, 0)
+    assert torch.equal(C2, C3)
+    assert np.array_equal(C2.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
+
+
+@pytest.mark.parametrize("R,stride,pad", [(3, 1, 1), (3, 2, 1), (1, 1, 0)])
+def test_twobit_conv_parity(R, stride, pad):
+    rnd = np.random.default_rng(R + stride)
+    Lw = rnd.integers(0, 3, size=(70, R, R, 64), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(3, 10, 9, 64), dtype=np.int8)
+    code = np.array([0, 1, 3], dtype=np.int8)
+    Wp = fatnn.pack_twobit(dev(code[Lw]), fatnn.OHWI)
+    Xp = fatnn.pack_twobit(dev(code[Lx]), fatnn.NHWC)
+    Y = fatnn.twobit_conv2d(Wp, Xp, 3, 64, 10, 9, 70, R, R, stride, pad)
+    assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, 0))
