@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the ternary hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of the headline workload (a
+ResNet-18-style 3x3 convolution, 128 -> 128 channels at 28x28, batch 32, ReLU-mode
+activations): pack the activation levels into plane words, then the implicit-GEMM
+ternary convolution with its int32 output and the fp32 per-channel scale/bias
+epilogue.  Weights are packed once before the timed region (the paper fixes them
+after training).  Inputs are seeded synthetic level tensors already resident in
+HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 4 SIMDs x 16 lanes = 16384 32-bit VALU lanes at 2.4 GHz.
+VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9
+# The reduced ternary inner product needs one three-input logic op and one popcount per
+# 32-bit plane word, two plane words per 32 elements: 4 lane-instructions per 32 MACs
+# (= 64 ops under the 2*M*N*K convention).  The conventional two-bit form needs 8.
+TERNARY_OPS_PER_LANE_INSTR = 64 / 4
+TWOBIT_OPS_PER_LANE_INSTR = 64 / 8
+TERNARY_PEAK_TOPS = VALU_LANE_OPS_PER_S * TERNARY_OPS_PER_LANE_INSTR / 1e12     # 629.1
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
+    return ap.parse_args()
+
+
+def time_kernel_ms(torch, fn, iters, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline_conv(case, seconds_target=12.0):
+    """The oracle as it stands, timed on the host cores on whole passes of the workload."""
+    import oracle
+    Lw, Lx = case.make()
+    t0 = time.perf_counter()
+    oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode)
+    first = time.perf_counter() - t0
+    reps = max(1, min(20, int(seconds_target / max(first, 1e-3))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode)
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": 2.0 * case.macs() / dt / 1e12, "unit": "Tops/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"{reps} full passes of {case.name} (batch {case.B}), {dt:.3f} s each"}
+
+
+def cpu_baseline_gemm(case, rows=64):
+    import numpy as np
+    import oracle
+    Lw, La = case.make()
+    sub = np.ascontiguousarray(Lw[:rows])
+    t0 = time.perf_counter()
+    oracle.ternary_gemm(sub, La, case.act_mode)
+    dt = time.perf_counter() - t0
+    return {"value": 2.0 * rows * case.N * case.K / dt / 1e12, "unit": "Tops/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"first {rows} of {case.M} weight rows against all columns, {dt:.2f} s"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X; this build has no multi-GPU path (columns would be sharded "
+              "with no collectives). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2008_05101_amd as fatnn
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    fatnn.lib()   # fail loudly now if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    extra = {}
+    if args.workload == "cfg2":
+        case = si.cfg2()
+        Lw, Lx = case.make()
+        scale, bias = case.make_scale_bias()
+        Lw_d = torch.from_numpy(Lw).to(dev)
+        Lx_d = torch.from_numpy(Lx).to(dev)
+        scale_d = torch.from_numpy(scale).to(dev)
+        bias_d = torch.from_numpy(bias).to(dev)
+        Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT, fatnn.OHWI)           # offline, once
+        Xp = torch.empty(fatnn.packed_bytes(fatnn.ACT, case.B * case.H * case.W, case.Cin), dtype=torch.uint8,
+                         device=dev)
+        Y = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.int32, device=dev)
+        Yf = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.float32, device=dev)
+        conv_args = (case.B, case.Cin, case.H, case.W, case.Cout, case.R, case.S, case.stride, case.pad,
+                     case.act_mode)
+
+        def pack_step():
+            fatnn.pack_ternary(Lx_d, fatnn.ACT, fatnn.NHWC, out=Xp)
+
+        def main_kernel():
+            fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y, scale=scale_d, bias=bias_d, out_f=Yf)
+
+        ops_per_step = 2.0 * case.macs()
+        config = {"workload": "cfg2: 3x3 conv 128->128 @28x28, batch 32, stride 1, pad 1 as implicit GEMM "
+                              "(M=128, N=25088, K=1152), ReLU-mode activations, int32 + fp32 scale/bias outputs; "
+                              "step = pack activations + conv",
+                  "M": case.M, "N": case.N, "K": case.K, "batch": case.B}
+        dominant = "plane_gemm_kernel (ternary, implicit-GEMM conv)"
+    else:
+        case = si.cfg4()
+        Lw, La = case.make()
+        Lw_d = torch.from_numpy(Lw).to(dev)
+        La_d = torch.from_numpy(La).to(dev)
+        Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT)
+        Ap = torch.empty(fatnn.packed_bytes(fatnn.ACT, case.N, case.K), dtype=torch.uint8, device=dev)
+        C = torch.empty((case.M, case.N), dtype=torch.int32, device=dev)
+
+        def pack_step():
+            fatnn.pack_ternary(La_d, fatnn.ACT, out=Ap)
+
+        def main_kernel():
+            fatnn.ternary_gemm(Wp, Ap, case.M, case.N, case.K, case.act_mode, out=C)
+
+        ops_per_step = 2.0 * case.macs()
+        config = {"workload": "cfg4: ternary GEMM M=N=K=8192, symmetric activations, int32 output; "
+                              "step = pack activations + GEMM",
+                  "M": case.M, "N": case.N, "K": case.K}
+        dominant = "plane_gemm_kernel (ternary GEMM)"
+
+    def step():
+        pack_step()
+        main_kernel()
+
+    # ---- warm-up, then exactly K timed steps ------------------------------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        pack_step()
+        starts[i].record()      # events on the stream the kernels are launched on (torch's current stream)
+        main_kernel()
+        stops[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
+    value = ops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    achieved = ops_per_step / (kernel_ms * 1e-3) / 1e12
+    roofline = {"bound": "alu", "kernel": dominant, "achieved": round(achieved, 2),
+                "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s", "frac": round(achieved / TERNARY_PEAK_TOPS, 4),
+                "traffic": None, "kernel_ms": round(kernel_ms, 5),
+                "peak_basis": "256 CU x 64 lanes x 2.4 GHz = 39.3 T lane-instr/s; 4 lane-instr per 64 ops"}
+
+    # ---- side measurements (outside the timed region) ---------------------------------------
+    if not args.no_extra:
+        try:
+            extra["pack_ms"] = round(time_kernel_ms(torch, pack_step, 50, 5), 5)
+            extra["main_kernel_ms_back_to_back"] = round(time_kernel_ms(torch, main_kernel, 50, 5), 5)
+            code = torch.tensor([0, 1, 3], dtype=torch.int8, device=dev)
+            if args.workload == "cfg2":
+                W2 = fatnn.pack_twobit(code[Lw_d.long()], fatnn.OHWI)
+                X2 = fatnn.pack_twobit(code[Lx_d.long()], fatnn.NHWC)
+                t2 = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *conv_args[:-1], out=Y), 50, 5)
+                t3 = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y), 50, 5)
+                extra["twobit_conv_ms"] = round(t2, 5)
+                extra["ternary_conv_int32_only_ms"] = round(t3, 5)
+                extra["speedup_vs_twobit"] = round(t2 / t3, 3)
+                # the large-GEMM roofline point
+                g = si.cfg4()
+                Gw = torch.randint(0, 3, (g.M, g.K), dtype=torch.int8, device=dev)
+                Ga = torch.randint(0, 3, (g.N, g.K), dtype=torch.int8, device=dev)
+                Gwp = fatnn.pack_ternary(Gw, fatnn.WEIGHT)
+                Gap = fatnn.pack_ternary(Ga, fatnn.ACT)
+                Gc = torch.empty((g.M, g.N), dtype=torch.int32, device=dev)
+                tg = time_kernel_ms(torch, lambda: fatnn.ternary_gemm(Gwp, Gap, g.M, g.N, g.K, 0, out=Gc), 10, 2)
+                G2w = fatnn.pack_twobit(code[Gw.long()])
+                G2a = fatnn.pack_twobit(code[Ga.long()])
+                tg2 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(G2w, G2a, g.M, g.N, g.K, 0, out=Gc), 10, 2)
+                gt = 2.0 * g.macs() / (tg * 1e-3) / 1e12
+                extra["gemm8192"] = {"ternary_ms": round(tg, 4), "ternary_tops": round(gt, 1),
+                                     "frac_of_alu_peak": round(gt / TERNARY_PEAK_TOPS, 4),
+                                     "twobit_ms": round(tg2, 4), "speedup_vs_twobit": round(tg2 / tg, 3)}
+                del Gw, Ga, Gwp, Gap, Gc, G2w, G2a
+                # int8 MFMA comparison point (context only): same operands as int8 values through the BLAS
+                try:
+                    a8 = (Lw_d.reshape(case.Cout, -1) - 1).contiguous()
+                    x8 = torch.randint(-1, 2, (case.K, case.N), dtype=torch.int8, device=dev)
+                    ti = time_kernel_ms(torch, lambda: torch._int_mm(a8, x8), 20, 3)
+                    extra["int8_mfma_gemm_same_shape_ms"] = round(ti, 5)
+                except Exception as exc:       # comparison only; never fatal
+                    extra["int8_mfma_gemm_same_shape_ms"] = f"unavailable: {type(exc).__name__}"
+            else:
+                W2 = fatnn.pack_twobit(code[Lw_d.long()])
+                A2 = fatnn.pack_twobit(code[La_d.long()])
+                t2 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(W2, A2, case.M, case.N, case.K, 0, out=C), 10, 2)
+                extra["twobit_gemm_ms"] = round(t2, 4)
+                extra["speedup_vs_twobit"] = round(t2 / extra["main_kernel_ms_back_to_back"], 3)
+                try:
+                    a8 = (Lw_d - 1).contiguous()
+                    x8 = (La_d - 1).t().contiguous()
+                    ti = time_kernel_ms(torch, lambda: torch._int_mm(a8, x8), 5, 2)
+                    extra["int8_mfma_gemm_ms"] = round(ti, 4)
+                except Exception as exc:
+                    extra["int8_mfma_gemm_ms"] = f"unavailable: {type(exc).__name__}"
+        except Exception as exc:   # side measurements must never lose the main line
+            extra["error"] = f"{type(exc).__name__}: {exc}"
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline_conv(case) if args.workload == "cfg2" else cpu_baseline_gemm(case)
+
+    line = {
+        "metric": "ternary GEMM Tops/s (2MNK) at 1 MI355X",
+        "value": round(value, 3),
+        "unit": "Tops/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 bit-planes, int32 accumulate",
+        "data": "synthetic",
+        "config": config,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "extra": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
