@@ -116,7 +116,7 @@ def main():
         scale_d = torch.from_numpy(scale).to(dev)
         bias_d = torch.from_numpy(bias).to(dev)
         Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT, fatnn.OHWI)           # offline, once
-        Xp = torch.empty(fatnn.packed_bytes(fatnn.ACT, case.B * case.H * case.W, case.Cin), dtype=torch.uint8,
+        Xp = torch.empty(fatnn.bordered_act_bytes(case.B, case.H, case.W, case.Cin, case.pad), dtype=torch.uint8,
                          device=dev)
         Y = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.int32, device=dev)
         Yf = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.float32, device=dev)
@@ -124,17 +124,18 @@ def main():
                      case.act_mode)
 
         def pack_step():
-            fatnn.pack_ternary(Lx_d, fatnn.ACT, fatnn.NHWC, out=Xp)
+            fatnn.pack_ternary_bordered(Lx_d, case.pad, case.act_mode, out=Xp)
 
         def main_kernel():
-            fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y, scale=scale_d, bias=bias_d, out_f=Yf)
+            fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y, scale=scale_d, bias=bias_d, out_f=Yf,
+                                 x_layout=fatnn.X_BORDERED)
 
         ops_per_step = 2.0 * case.macs()
         config = {"workload": "cfg2: 3x3 conv 128->128 @28x28, batch 32, stride 1, pad 1 as implicit GEMM "
                               "(M=128, N=25088, K=1152), ReLU-mode activations, int32 + fp32 scale/bias outputs; "
                               "step = pack activations + conv",
                   "M": case.M, "N": case.N, "K": case.K, "batch": case.B}
-        dominant = "plane_gemm_kernel (ternary, implicit-GEMM conv)"
+        dominant = "stream_conv_kernel (ternary, weight-stationary implicit-GEMM conv)"
     else:
         case = si.cfg4()
         Lw, La = case.make()
@@ -192,10 +193,12 @@ def main():
             extra["main_kernel_ms_back_to_back"] = round(time_kernel_ms(torch, main_kernel, 50, 5), 5)
             code = torch.tensor([0, 1, 3], dtype=torch.int8, device=dev)
             if args.workload == "cfg2":
-                W2 = fatnn.pack_twobit(code[Lw_d.long()], fatnn.OHWI)
-                X2 = fatnn.pack_twobit(code[Lx_d.long()], fatnn.NHWC)
-                t2 = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *conv_args[:-1], out=Y), 50, 5)
-                t3 = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y), 50, 5)
+                W2 = fatnn.pack_twobit(code[Lw_d.long()], fatnn.WEIGHT, fatnn.OHWI)
+                X2 = fatnn.pack_twobit_bordered(code[Lx_d.long()], case.pad)
+                t2 = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *conv_args[:-1], out=Y,
+                                                                       x_layout=fatnn.X_BORDERED), 50, 5)
+                t3 = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y,
+                                                                        x_layout=fatnn.X_BORDERED), 50, 5)
                 extra["twobit_conv_ms"] = round(t2, 5)
                 extra["ternary_conv_int32_only_ms"] = round(t3, 5)
                 extra["speedup_vs_twobit"] = round(t2 / t3, 3)

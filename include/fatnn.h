@@ -66,6 +66,7 @@ enum {                                                    /* layout of a level t
     FATNN_OIHW = 3,       /* dims = {O, C, R, S}: same packed result as OHWI (gathering, slow path)   */
     FATNN_NCHW = 4        /* dims = {B, C, H, W}: same packed result as NHWC (gathering, slow path)   */
 };
+enum { FATNN_X_PLAIN = 0, FATNN_X_BORDERED = 1 };         /* layout of packed conv activations        */
 enum { FATNN_BASIS_TERNARY = 0, FATNN_BASIS_UNIFORM = 1 };/* two-bit basis, see fatnn_twobit_gemm     */
 
 /* Largest supported extents: rows, columns < 2^31; K <= 2^24 (keeps |C| <= 2K exact in fp32 too). */
@@ -77,11 +78,18 @@ int64_t fatnn_words_per_row(int64_t K);
 /* Bytes of a packed buffer of `rows` rows of K elements.  role = FATNN_WEIGHT adds
  * the per-row constants (see file header).  Returns 0 on invalid arguments.
  * Layout: rows*Kw pairs of uint32, then (weights only) at the next multiple of
- * 256 bytes int32 nnz[rows] followed by int32 npos[rows]. */
+ * 256 bytes int32 nnz[rows] followed by int32 npos[rows], then at the next multiple
+ * of 256 bytes the lane-interleaved copy (fatnn_weight_interleaved_offset). */
 size_t fatnn_packed_bytes(int role, int64_t rows, int64_t K);
 
 /* Byte offset of the per-row constants inside a packed weight buffer. */
 size_t fatnn_weight_consts_offset(int64_t rows, int64_t K);
+
+/* Byte offset of the second, lane-interleaved copy of the plane words inside a packed
+ * weight buffer: [ceil(rows/64)][Kw][64] pairs, rows past the end zero.  The
+ * column-streaming convolution kernel reads the weights of 64 output channels with
+ * one coalesced load per k-word from it. */
+size_t fatnn_weight_interleaved_offset(int64_t rows, int64_t K);
 
 /*
  * Algorithm 1, step 1 (data packing), from level indices.
@@ -101,6 +109,22 @@ int fatnn_pack_ternary(const int8_t *levels, int layout, const int64_t dims[4], 
                        void *packed, size_t packed_bytes, int32_t *n_invalid, void *stream);
 
 /*
+ * The same packing for convolution inputs, into the BORDERED layout
+ *     [B][H + 2*border][W + 2*border][C/32] word pairs  (+ FATNN_BORDER_SLACK_PIXELS pixels),
+ * where the ring of `border` pixels around every image and the slack behind the last
+ * image hold the VALUE 0 under `act_mode` (level 1 in FATNN_SYM, level 0 in FATNN_RELU).
+ * With border = the convolution's padding no tap ever falls outside the stored image,
+ * which lets fatnn_ternary_conv2d run its fastest kernel; border = 0 is the plain
+ * pixel order plus the slack (for 1x1 convolutions).
+ *   levels   device int8, NHWC, dims = {B, H, W, C}, C a multiple of 32, 16-byte aligned
+ *   packed   device, 16-byte aligned, at least fatnn_bordered_act_bytes() bytes
+ */
+#define FATNN_BORDER_SLACK_PIXELS 64
+size_t fatnn_bordered_act_bytes(int64_t B, int64_t H, int64_t W, int64_t C, int border);
+int fatnn_pack_ternary_bordered(const int8_t *levels, const int64_t dims[4], int border, int act_mode,
+                                void *packed, size_t packed_bytes, int32_t *n_invalid, void *stream);
+
+/*
  * Ternary GEMM through Eq. 3:  C[m][n] = sum_k w[m][k] * a[n][k].
  *   Wp            packed weights  [M][Kw] (+ constants), from fatnn_pack_ternary(role WEIGHT)
  *   Ap            packed activations [N][Kw], from fatnn_pack_ternary(role ACT)
@@ -118,14 +142,16 @@ int fatnn_ternary_gemm(const void *Wp, const void *Ap, int64_t M, int64_t N, int
  * Ternary convolution as an implicit GEMM (Supplementary S1: im2col + gemm, here
  * without materialising the matrix).
  *   Wp            packed weights from layout OHWI/OIHW: [Cout][R*S*Cin/32] (+ constants)
- *   Xp            packed activations from layout NHWC/NCHW: [B][H][W][Cin/32]
+ *   Xp, x_layout  packed activations: FATNN_X_PLAIN = [B][H][W][Cin/32] from
+ *                 fatnn_pack_ternary (NHWC/NCHW); FATNN_X_BORDERED = the bordered layout of
+ *                 fatnn_pack_ternary_bordered with border == pad and the same act_mode
  *   Y, Yf         int32 / fp32 NHWC outputs [B][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
  *   Padding is the VALUE 0 in either act_mode.
  * Supported: R = S in {1, 3}, stride in {1, 2}, pad in {0, 1} with pad <= R/2,
  * Cin a multiple of 32; anything else returns FATNN_ERR_UNSUPPORTED.
  */
-int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
-                         int64_t Cout, int R, int S, int stride, int pad, int act_mode, int32_t *Y,
+int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
+                         int64_t W, int64_t Cout, int R, int S, int stride, int pad, int act_mode, int32_t *Y,
                          const float *scale, const float *bias, float *Yf, void *stream);
 
 /*
@@ -135,18 +161,23 @@ int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int64_t B, int64_t Cin,
  * O(2N) claim (Remark 1) can be measured on the same chip with the same tiling.
  *
  * Codes q = 2*b1 + b0 in {0,1,2,3}; plane words .x = b1, .y = b0; tail bits 0.
+ * fatnn_pack_twobit takes the same layouts, roles and buffer sizes as
+ * fatnn_pack_ternary (role WEIGHT adds the interleaved copy; the constants are unused).
  * The value of a code is  alpha0*(2*b0-1) + alpha1*(2*b1-1):
  *   FATNN_BASIS_TERNARY  alpha = (1/2, 1/2): 00,01,10,11 -> -1,0,0,+1 (Table 1's codec)
  *   FATNN_BASIS_UNIFORM  alpha = (1, 2):     00,01,10,11 -> -3,-1,+1,+3
  * C[m][n] = sum_k value(w) * value(a), int32.
  */
-int fatnn_pack_twobit(const int8_t *codes, int layout, const int64_t dims[4], void *packed,
+int fatnn_pack_twobit(const int8_t *codes, int layout, const int64_t dims[4], int role, void *packed,
                       size_t packed_bytes, int32_t *n_invalid, void *stream);
 int fatnn_twobit_gemm(const void *Wp, const void *Ap, int64_t M, int64_t N, int64_t K, int basis,
                       int32_t *C, int64_t ldc, void *stream);
+/* Bordered packing of two-bit codes; the ring holds code 01 (value 0 in the TERNARY basis). */
+int fatnn_pack_twobit_bordered(const int8_t *codes, const int64_t dims[4], int border, void *packed,
+                               size_t packed_bytes, int32_t *n_invalid, void *stream);
 /* TERNARY basis only (the padded taps need a code of value 0). */
-int fatnn_twobit_conv2d(const void *Wp, const void *Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
-                        int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t *Y,
+int fatnn_twobit_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
+                        int64_t W, int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t *Y,
                         void *stream);
 
 const char *fatnn_status_str(int status);

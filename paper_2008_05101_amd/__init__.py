@@ -6,7 +6,8 @@ raises if the library has not been built (``python -m paper_2008_05101_amd.build
 There is no CPU fallback.
 """
 from .binding import (  # noqa: F401
-    ACT, BASIS_TERNARY, BASIS_UNIFORM, NCHW, NHWC, OHWI, OIHW, RELU, ROWMAJOR_K, SYM, WEIGHT,
-    FatnnError, lib, pack_ternary, pack_twobit, packed_bytes, status_str, ternary_conv2d, ternary_gemm,
-    twobit_conv2d, twobit_gemm, weight_consts_offset, words_per_row,
+    ACT, BASIS_TERNARY, BASIS_UNIFORM, NCHW, NHWC, OHWI, OIHW, RELU, ROWMAJOR_K, SYM, WEIGHT, X_BORDERED, X_PLAIN,
+    FatnnError, bordered_act_bytes, lib, pack_ternary, pack_ternary_bordered, pack_twobit, pack_twobit_bordered,
+    packed_bytes, status_str, ternary_conv2d, ternary_gemm,
+    twobit_conv2d, twobit_gemm, weight_consts_offset, weight_interleaved_offset, words_per_row,
 )

@@ -16,9 +16,12 @@ WEIGHT, ACT = 0, 1
 SYM, RELU = 0, 1
 ROWMAJOR_K, NHWC, OHWI, OIHW, NCHW = 0, 1, 2, 3, 4
 BASIS_TERNARY, BASIS_UNIFORM = 0, 1
+X_PLAIN, X_BORDERED = 0, 1
 
 EXPORTS = [
-    "fatnn_words_per_row", "fatnn_packed_bytes", "fatnn_weight_consts_offset", "fatnn_pack_ternary",
+    "fatnn_words_per_row", "fatnn_packed_bytes", "fatnn_weight_consts_offset",
+    "fatnn_weight_interleaved_offset", "fatnn_pack_ternary", "fatnn_bordered_act_bytes",
+    "fatnn_pack_ternary_bordered", "fatnn_pack_twobit_bordered",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
     "fatnn_twobit_conv2d", "fatnn_status_str", "fatnn_version",
 ]
@@ -49,13 +52,20 @@ def lib() -> ctypes.CDLL:
         l.fatnn_packed_bytes.restype = sz
         l.fatnn_weight_consts_offset.argtypes = [i64, i64]
         l.fatnn_weight_consts_offset.restype = sz
+        l.fatnn_weight_interleaved_offset.argtypes = [i64, i64]
+        l.fatnn_weight_interleaved_offset.restype = sz
         dims4 = ctypes.POINTER(i64)
         l.fatnn_pack_ternary.argtypes = [vp, i32, dims4, i32, vp, sz, vp, vp]
-        l.fatnn_pack_twobit.argtypes = [vp, i32, dims4, vp, sz, vp, vp]
+        l.fatnn_pack_twobit.argtypes = [vp, i32, dims4, i32, vp, sz, vp, vp]
         l.fatnn_ternary_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, i64, vp]
-        l.fatnn_ternary_conv2d.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+        l.fatnn_ternary_conv2d.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp,
+                                           vp, vp]
+        l.fatnn_bordered_act_bytes.argtypes = [i64, i64, i64, i64, i32]
+        l.fatnn_bordered_act_bytes.restype = sz
+        l.fatnn_pack_ternary_bordered.argtypes = [vp, dims4, i32, i32, vp, sz, vp, vp]
+        l.fatnn_pack_twobit_bordered.argtypes = [vp, dims4, i32, vp, sz, vp, vp]
         l.fatnn_twobit_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp]
-        l.fatnn_twobit_conv2d.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
+        l.fatnn_twobit_conv2d.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
         l.fatnn_status_str.argtypes = [i32]
         l.fatnn_status_str.restype = ctypes.c_char_p
         l.fatnn_version.restype = i32
@@ -102,6 +112,10 @@ def weight_consts_offset(rows: int, K: int) -> int:
     return int(lib().fatnn_weight_consts_offset(rows, K))
 
 
+def weight_interleaved_offset(rows: int, K: int) -> int:
+    return int(lib().fatnn_weight_interleaved_offset(rows, K))
+
+
 def _rows_k(layout: int, dims: Sequence[int]) -> Tuple[int, int]:
     d = list(dims)
     if layout == ROWMAJOR_K:
@@ -142,16 +156,49 @@ def pack_ternary(levels: torch.Tensor, role: int, layout: int = ROWMAJOR_K,
     return out
 
 
-def pack_twobit(codes: torch.Tensor, layout: int = ROWMAJOR_K, out: Optional[torch.Tensor] = None,
-                n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+def pack_twobit(codes: torch.Tensor, role: int = ACT, layout: int = ROWMAJOR_K,
+                out: Optional[torch.Tensor] = None, n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
     codes = _dev(codes, torch.int8, "codes")
     dims, shape = _dims4(layout, codes)
     rows, K = _rows_k(layout, shape)
-    nbytes = packed_bytes(ACT, rows, K) if K >= 1 else 0
+    nbytes = packed_bytes(role, rows, K) if K >= 1 else 0
     if out is None:
         out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=codes.device)
-    _check(lib().fatnn_pack_twobit(_ptr(codes), layout, dims, _ptr(out), out.numel(), _ptr(n_invalid),
+    _check(lib().fatnn_pack_twobit(_ptr(codes), layout, dims, role, _ptr(out), out.numel(), _ptr(n_invalid),
                                    _stream()), "fatnn_pack_twobit")
+    return out
+
+
+def bordered_act_bytes(B: int, H: int, W: int, C: int, border: int) -> int:
+    return int(lib().fatnn_bordered_act_bytes(B, H, W, C, border))
+
+
+def pack_ternary_bordered(levels: torch.Tensor, border: int, act_mode: int, out: Optional[torch.Tensor] = None,
+                          n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fatnn_pack_ternary_bordered: NHWC int8 levels -> bordered packed activations."""
+    levels = _dev(levels, torch.int8, "levels")
+    if levels.dim() != 4:
+        raise ValueError("levels must be NHWC")
+    B, H, W, C = levels.shape
+    dims = (ctypes.c_int64 * 4)(B, H, W, C)
+    if out is None:
+        out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8, device=levels.device)
+    _check(lib().fatnn_pack_ternary_bordered(_ptr(levels), dims, border, act_mode, _ptr(out), out.numel(),
+                                             _ptr(n_invalid), _stream()), "fatnn_pack_ternary_bordered")
+    return out
+
+
+def pack_twobit_bordered(codes: torch.Tensor, border: int, out: Optional[torch.Tensor] = None,
+                         n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+    codes = _dev(codes, torch.int8, "codes")
+    if codes.dim() != 4:
+        raise ValueError("codes must be NHWC")
+    B, H, W, C = codes.shape
+    dims = (ctypes.c_int64 * 4)(B, H, W, C)
+    if out is None:
+        out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8, device=codes.device)
+    _check(lib().fatnn_pack_twobit_bordered(_ptr(codes), dims, border, _ptr(out), out.numel(), _ptr(n_invalid),
+                                            _stream()), "fatnn_pack_twobit_bordered")
     return out
 
 
@@ -179,14 +226,14 @@ def ternary_conv2d(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H: int,
                    R: int = 3, S: int = 3, stride: int = 1, pad: int = 1, act_mode: int = RELU,
                    out: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
                    bias: Optional[torch.Tensor] = None, out_f: Optional[torch.Tensor] = None,
-                   want_int: bool = True):
+                   want_int: bool = True, x_layout: int = X_PLAIN):
     """fatnn_ternary_conv2d.  Returns (Y int32 NHWC or None, Yf fp32 NHWC or None)."""
     Ho, Wo = _conv_out_hw(H, W, R, S, stride, pad)
     if out is None and want_int:
         out = torch.empty((B, Ho, Wo, Cout), dtype=torch.int32, device=Wp.device)
     if scale is not None and out_f is None:
         out_f = torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device=Wp.device)
-    _check(lib().fatnn_ternary_conv2d(_ptr(Wp), _ptr(Xp), B, Cin, H, W, Cout, R, S, stride, pad, act_mode,
+    _check(lib().fatnn_ternary_conv2d(_ptr(Wp), _ptr(Xp), x_layout, B, Cin, H, W, Cout, R, S, stride, pad, act_mode,
                                       _ptr(out), _ptr(scale), _ptr(bias), _ptr(out_f), _stream()),
            "fatnn_ternary_conv2d")
     return out, out_f
@@ -204,10 +251,10 @@ def twobit_gemm(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, basi
 
 def twobit_conv2d(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H: int, W: int, Cout: int,
                   R: int = 3, S: int = 3, stride: int = 1, pad: int = 1, basis: int = BASIS_TERNARY,
-                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                  out: Optional[torch.Tensor] = None, x_layout: int = X_PLAIN) -> torch.Tensor:
     Ho, Wo = _conv_out_hw(H, W, R, S, stride, pad)
     if out is None:
         out = torch.empty((B, Ho, Wo, Cout), dtype=torch.int32, device=Wp.device)
-    _check(lib().fatnn_twobit_conv2d(_ptr(Wp), _ptr(Xp), B, Cin, H, W, Cout, R, S, stride, pad, basis,
+    _check(lib().fatnn_twobit_conv2d(_ptr(Wp), _ptr(Xp), x_layout, B, Cin, H, W, Cout, R, S, stride, pad, basis,
                                      _ptr(out), _stream()), "fatnn_twobit_conv2d")
     return out

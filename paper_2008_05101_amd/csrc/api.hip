@@ -4,6 +4,8 @@
 #include "../../include/fatnn.h"
 #include "fatnn_device.h"
 
+#include <stdlib.h>
+
 using namespace fatnn;
 
 namespace {
@@ -85,13 +87,12 @@ int pack_shape(int layout, const int64_t dims[4], PackShape* out) {
     return FATNN_OK;
 }
 
-int pack_common(const int8_t* levels, int layout, const int64_t dims[4], int kind, void* packed,
+int pack_common(const int8_t* levels, int layout, const int64_t dims[4], int kind, int role, void* packed,
                 size_t packed_bytes, int32_t* n_invalid, void* stream) {
     if (dims == nullptr) return FATNN_ERR_NULL;
     PackShape s;
     int rc = pack_shape(layout, dims, &s);
     if (rc != FATNN_OK) return rc;
-    const int role = (kind == PACK_WEIGHT) ? FATNN_WEIGHT : FATNN_ACT;
     if (s.rows == 0) return FATNN_OK;
     if (levels == nullptr || packed == nullptr) return FATNN_ERR_NULL;
     if (!aligned(packed, 16)) return FATNN_ERR_ALIGN;
@@ -102,11 +103,15 @@ int pack_common(const int8_t* levels, int layout, const int64_t dims[4], int kin
     int lrc = s.gather ? launch_pack_gather(levels, s.rows, s.K, s.g, kind, out, n_invalid, st)
                        : launch_pack_contiguous(levels, s.rows, s.K, kind, out, n_invalid, st);
     if (lrc != 0) return FATNN_ERR_HIP;
-    if (kind == PACK_WEIGHT) {
+    if (role == FATNN_WEIGHT) {
         const int64_t Kw = fatnn_words_per_row(s.K);
-        int32_t* consts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(packed) +
-                                                     fatnn_weight_consts_offset(s.rows, s.K));
-        if (launch_row_constants(out, s.rows, Kw, consts, consts + s.rows, st) != 0) return FATNN_ERR_HIP;
+        char* base = reinterpret_cast<char*>(packed);
+        if (kind == PACK_WEIGHT) {
+            int32_t* consts = reinterpret_cast<int32_t*>(base + fatnn_weight_consts_offset(s.rows, s.K));
+            if (launch_row_constants(out, s.rows, Kw, consts, consts + s.rows, st) != 0) return FATNN_ERR_HIP;
+        }
+        plane2* inter = reinterpret_cast<plane2*>(base + fatnn_weight_interleaved_offset(s.rows, s.K));
+        if (launch_interleave_weights(out, s.rows, Kw, inter, st) != 0) return FATNN_ERR_HIP;
     }
     return FATNN_OK;
 }
@@ -155,6 +160,110 @@ void set_ternary_consts(GemmParams& p, const void* Wp, int64_t M, int64_t K, int
     }
 }
 
+// Which convolution kernel serves a call.  FATNN_CONV_KERNEL=tiled overrides the
+// choice (for measurements); FATNN_STREAM_WPS sets the wavefronts per SIMD of the
+// streaming kernel.
+bool want_stream(int op, int R, int S, int Cw, int stride) {
+    if (!stream_supported(op, R, S, Cw, stride)) return false;
+    const char* e = getenv("FATNN_CONV_KERNEL");
+    if (e != nullptr && e[0] == 't') return false;
+    return true;
+}
+
+// Number of ranges of pixel groups (= wavefronts per block of 64 output channels).  All
+// wavefronts are meant to be resident at once, the same number on every SIMD, and
+// each should see enough groups to amortise loading its weights.
+int stream_ranges(int64_t M, int64_t ngroups, int64_t group_size, int64_t Kw) {
+    const int64_t mblocks = (M + 63) / 64;
+    const int64_t vgprs = 2 * Kw + 24;
+    int64_t occ = 512 / vgprs;
+    if (occ > 8) occ = 8;
+    if (occ < 1) occ = 1;
+    int64_t wps = (ngroups * group_size * mblocks + 1024 * 16 - 1) / (1024 * 16);
+    const char* e = getenv("FATNN_STREAM_WPS");
+    if (e != nullptr && atoi(e) > 0) wps = atoi(e);
+    if (wps > occ) wps = occ;
+    if (wps < 1) wps = 1;
+    int64_t ranges = (1024 * wps) / mblocks;
+    if (ranges < 1) ranges = 1;
+    if (ranges > ngroups) ranges = ngroups;
+    return (int)ranges;
+}
+
+int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Cin, int64_t H, int64_t W,
+             int64_t Cout, int R, int S, int stride, int pad, const ConvShape& cs, int op, int act_mode, int32_t* Y,
+             const float* scale, const float* bias, float* Yf, void* stream) {
+    const int Cw = (int)(Cin / 32);
+    const uint32_t pad_y = (op == OP_TERNARY && act_mode == FATNN_RELU) ? 0u : 0xFFFFFFFFu;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const bool bordered = x_layout == FATNN_X_BORDERED;
+    // in the bordered layout the padding is physical: a larger image convolved without padding
+    const int64_t Hs = bordered ? H + 2 * pad : H, Ws = bordered ? W + 2 * pad : W;
+    const int pad_s = bordered ? 0 : pad;
+    const int64_t stored_bytes = (B * Hs * Ws + FATNN_BORDER_SLACK_PIXELS) * Cw * (int64_t)sizeof(plane2);
+    if (bordered && stored_bytes < 0xFFFFFFFFLL && want_stream(op, R, S, Cw, stride)) {
+        StreamParams q{};
+        q.Wi = reinterpret_cast<const plane2*>(reinterpret_cast<const char*>(Wp) +
+                                               fatnn_weight_interleaved_offset(Cout, cs.K));
+        q.A = reinterpret_cast<const uint32_t*>(Xp);
+        if (op == OP_TERNARY) {
+            GemmParams t{};
+            set_ternary_consts(t, Wp, Cout, cs.K, act_mode);
+            q.rowc = t.rowc;
+            q.cmul = t.cmul;
+        }
+        q.K = (int32_t)cs.K;
+        q.M = (int32_t)Cout;
+        q.Kw = (int32_t)(cs.K / 32);
+        q.C = Y; q.Cf = Yf; q.ldc_n = Cout;
+        q.scale = scale; q.bias = bias;
+        q.B = (int32_t)B; q.Hp = (int32_t)Hs; q.Wp = (int32_t)Ws; q.Ho = (int32_t)cs.Ho; q.Wo = (int32_t)cs.Wo;
+        const int U = stream_group_size(R, Cw, stride);
+        const int64_t ngroups = B * cs.Ho * ((cs.Wo + U - 1) / U);
+        const int ranges = stream_ranges(Cout, ngroups, U, q.Kw);
+        return launch_stream_conv(q, op, R, Cw, stride, ranges, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+    }
+    GemmParams p{};
+    p.W = reinterpret_cast<const plane2*>(Wp);
+    p.A = reinterpret_cast<const plane2*>(Xp);
+    if (op == OP_TERNARY) set_ternary_consts(p, Wp, Cout, cs.K, act_mode);
+    p.K = (int32_t)cs.K;
+    p.M = (int32_t)Cout;
+    p.N = (int32_t)cs.N;
+    p.Kw = (int32_t)(cs.K / 32);
+    p.C = Y; p.ldc_m = 1; p.ldc_n = Cout;
+    p.Cf = Yf; p.ldf_m = 1; p.ldf_n = Cout;
+    p.scale = scale; p.bias = bias;
+    p.is_conv = 1;
+    p.B = (int32_t)B; p.H = (int32_t)Hs; p.Wd = (int32_t)Ws; p.Cw = Cw;
+    p.Ho = (int32_t)cs.Ho; p.Wo = (int32_t)cs.Wo; p.R = R; p.S = S; p.stride = stride; p.pad = pad_s;
+    // a padded tap is the value 0: level 1 = codec 01 in symmetric mode (and in the two-bit
+    // ternary basis), level 0 = codec 00 in ReLU mode
+    p.pad_x = 0u;
+    p.pad_y = pad_y;
+    return launch_gemm(p, op, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+}
+
+int pack_bordered_common(const int8_t* levels, const int64_t dims[4], int border, int kind, plane2 border_word,
+                         void* packed, size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    if (dims == nullptr) return FATNN_ERR_NULL;
+    const int64_t B = dims[0], H = dims[1], W = dims[2], C = dims[3];
+    if (B < 0 || H < 1 || W < 1 || C < 1) return FATNN_ERR_SHAPE;
+    if (border < 0 || border > 1) return FATNN_ERR_UNSUPPORTED;
+    if (C % 32 != 0) return FATNN_ERR_UNSUPPORTED;
+    if (H > 65535 || W > 65535 || C > FATNN_MAX_K) return FATNN_ERR_SIZE;
+    if (B != 0 && (H + 2) * (W + 2) > kMaxRows / B) return FATNN_ERR_SIZE;
+    if (levels == nullptr && B > 0) return FATNN_ERR_NULL;
+    if (packed == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(packed, 16) || !aligned(levels, 16) || !aligned(n_invalid, 4)) return FATNN_ERR_ALIGN;
+    if (packed_bytes < fatnn_bordered_act_bytes(B, H, W, C, border)) return FATNN_ERR_SIZE;
+    return launch_pack_bordered(levels, B, H, W, C, border, kind, border_word, FATNN_BORDER_SLACK_PIXELS,
+                                reinterpret_cast<plane2*>(packed), n_invalid,
+                                reinterpret_cast<hipStream_t>(stream)) == 0
+               ? FATNN_OK
+               : FATNN_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -170,19 +279,26 @@ size_t fatnn_packed_bytes(int role, int64_t rows, int64_t K) {
     if (rows < 0 || K < 1 || (role != FATNN_WEIGHT && role != FATNN_ACT)) return 0;
     const size_t words = (size_t)rows * (size_t)fatnn_words_per_row(K) * sizeof(plane2);
     if (role == FATNN_ACT) return words;
+    return fatnn_weight_interleaved_offset(rows, K) +
+           (size_t)((rows + 63) / 64) * 64 * (size_t)fatnn_words_per_row(K) * sizeof(plane2);
+}
+
+size_t fatnn_weight_interleaved_offset(int64_t rows, int64_t K) {
+    if (rows < 0 || K < 1) return 0;
     return fatnn_weight_consts_offset(rows, K) + round_up((size_t)rows * 2 * sizeof(int32_t), 256);
 }
 
 int fatnn_pack_ternary(const int8_t* levels, int layout, const int64_t dims[4], int role, void* packed,
                        size_t packed_bytes, int32_t* n_invalid, void* stream) {
     if (role != FATNN_WEIGHT && role != FATNN_ACT) return FATNN_ERR_UNSUPPORTED;
-    return pack_common(levels, layout, dims, role == FATNN_WEIGHT ? PACK_WEIGHT : PACK_ACT, packed,
+    return pack_common(levels, layout, dims, role == FATNN_WEIGHT ? PACK_WEIGHT : PACK_ACT, role, packed,
                        packed_bytes, n_invalid, stream);
 }
 
-int fatnn_pack_twobit(const int8_t* codes, int layout, const int64_t dims[4], void* packed,
+int fatnn_pack_twobit(const int8_t* codes, int layout, const int64_t dims[4], int role, void* packed,
                       size_t packed_bytes, int32_t* n_invalid, void* stream) {
-    return pack_common(codes, layout, dims, PACK_TWOBIT, packed, packed_bytes, n_invalid, stream);
+    if (role != FATNN_WEIGHT && role != FATNN_ACT) return FATNN_ERR_UNSUPPORTED;
+    return pack_common(codes, layout, dims, PACK_TWOBIT, role, packed, packed_bytes, n_invalid, stream);
 }
 
 int fatnn_ternary_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int act_mode,
@@ -215,9 +331,33 @@ int fatnn_ternary_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int
     return launch_gemm(p, OP_TERNARY, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
 }
 
-int fatnn_ternary_conv2d(const void* Wp, const void* Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
-                         int64_t Cout, int R, int S, int stride, int pad, int act_mode, int32_t* Y,
+size_t fatnn_bordered_act_bytes(int64_t B, int64_t H, int64_t W, int64_t C, int border) {
+    if (B < 0 || H < 1 || W < 1 || C < 1 || C % 32 != 0 || border < 0 || border > 1) return 0;
+    return (size_t)(B * (H + 2 * border) * (W + 2 * border) + FATNN_BORDER_SLACK_PIXELS) * (size_t)(C / 32) *
+           sizeof(plane2);
+}
+
+int fatnn_pack_ternary_bordered(const int8_t* levels, const int64_t dims[4], int border, int act_mode, void* packed,
+                                size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
+    plane2 bw;
+    bw.x = 0u;
+    bw.y = act_mode == FATNN_SYM ? 0xFFFFFFFFu : 0u;   // level 1 = codec 01  |  level 0 = codec 00
+    return pack_bordered_common(levels, dims, border, PACK_ACT, bw, packed, packed_bytes, n_invalid, stream);
+}
+
+int fatnn_pack_twobit_bordered(const int8_t* codes, const int64_t dims[4], int border, void* packed,
+                               size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    plane2 bw;
+    bw.x = 0u;
+    bw.y = 0xFFFFFFFFu;   // code 01
+    return pack_bordered_common(codes, dims, border, PACK_TWOBIT, bw, packed, packed_bytes, n_invalid, stream);
+}
+
+int fatnn_ternary_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
+                         int64_t W, int64_t Cout, int R, int S, int stride, int pad, int act_mode, int32_t* Y,
                          const float* scale, const float* bias, float* Yf, void* stream) {
+    if (x_layout != FATNN_X_PLAIN && x_layout != FATNN_X_BORDERED) return FATNN_ERR_UNSUPPORTED;
     ConvShape cs;
     int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
     if (rc != FATNN_OK) return rc;
@@ -229,24 +369,8 @@ int fatnn_ternary_conv2d(const void* Wp, const void* Xp, int64_t B, int64_t Cin,
     if (!aligned(Wp, 16) || !aligned(Xp, 16) || !aligned(Y, 4) || !aligned(Yf, 4) || !aligned(scale, 4) ||
         !aligned(bias, 4))
         return FATNN_ERR_ALIGN;
-    GemmParams p{};
-    p.W = reinterpret_cast<const plane2*>(Wp);
-    p.A = reinterpret_cast<const plane2*>(Xp);
-    set_ternary_consts(p, Wp, Cout, cs.K, act_mode);
-    p.K = (int32_t)cs.K;
-    p.M = (int32_t)Cout;
-    p.N = (int32_t)cs.N;
-    p.Kw = (int32_t)(cs.K / 32);
-    p.C = Y; p.ldc_m = 1; p.ldc_n = Cout;
-    p.Cf = Yf; p.ldf_m = 1; p.ldf_n = Cout;
-    p.scale = scale; p.bias = bias;
-    p.is_conv = 1;
-    p.B = (int32_t)B; p.H = (int32_t)H; p.Wd = (int32_t)W; p.Cw = (int32_t)(Cin / 32);
-    p.Ho = (int32_t)cs.Ho; p.Wo = (int32_t)cs.Wo; p.R = R; p.S = S; p.stride = stride; p.pad = pad;
-    // a padded tap is the value 0: level 1 = codec 01 in symmetric mode, level 0 = codec 00 in ReLU mode
-    p.pad_x = 0u;
-    p.pad_y = (act_mode == FATNN_SYM) ? 0xFFFFFFFFu : 0u;
-    return launch_gemm(p, OP_TERNARY, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+    return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TERNARY, act_mode, Y, scale,
+                    bias, Yf, stream);
 }
 
 int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int basis, int32_t* C,
@@ -273,8 +397,10 @@ int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int6
     return launch_gemm(p, op, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
 }
 
-int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
-                        int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t* Y, void* stream) {
+int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
+                        int64_t W, int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t* Y,
+                        void* stream) {
+    if (x_layout != FATNN_X_PLAIN && x_layout != FATNN_X_BORDERED) return FATNN_ERR_UNSUPPORTED;
     ConvShape cs;
     int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
     if (rc != FATNN_OK) return rc;
@@ -283,21 +409,8 @@ int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int64_t B, int64_t Cin, 
     if (Y == nullptr) return FATNN_ERR_NULL;
     if (Wp == nullptr || Xp == nullptr) return FATNN_ERR_NULL;
     if (!aligned(Wp, 16) || !aligned(Xp, 16) || !aligned(Y, 4)) return FATNN_ERR_ALIGN;
-    GemmParams p{};
-    p.W = reinterpret_cast<const plane2*>(Wp);
-    p.A = reinterpret_cast<const plane2*>(Xp);
-    p.K = (int32_t)cs.K;
-    p.M = (int32_t)Cout;
-    p.N = (int32_t)cs.N;
-    p.Kw = (int32_t)(cs.K / 32);
-    p.C = Y; p.ldc_m = 1; p.ldc_n = Cout;
-    p.is_conv = 1;
-    p.B = (int32_t)B; p.H = (int32_t)H; p.Wd = (int32_t)W; p.Cw = (int32_t)(Cin / 32);
-    p.Ho = (int32_t)cs.Ho; p.Wo = (int32_t)cs.Wo; p.R = R; p.S = S; p.stride = stride; p.pad = pad;
-    p.pad_x = 0u;            // code 01: the value 0 of Table 1
-    p.pad_y = 0xFFFFFFFFu;
-    return launch_gemm(p, OP_TWOBIT_TERNARY, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK
-                                                                                         : FATNN_ERR_HIP;
+    return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TWOBIT_TERNARY, FATNN_SYM, Y,
+                    nullptr, nullptr, nullptr, stream);
 }
 
 const char* fatnn_status_str(int status) {

@@ -31,6 +31,7 @@ int launch_pack_contiguous(const int8_t* levels, int64_t rows, int64_t K, int ki
                            int32_t* n_invalid, hipStream_t stream);
 int launch_pack_gather(const int8_t* levels, int64_t rows, int64_t K, GatherDesc g, int kind,
                        plane2* packed, int32_t* n_invalid, hipStream_t stream);
+int launch_interleave_weights(const plane2* packed, int64_t rows, int64_t Kw, plane2* inter, hipStream_t stream);
 int launch_row_constants(const plane2* packed, int64_t rows, int64_t Kw, int32_t* nnz, int32_t* npos,
                          hipStream_t stream);
 
@@ -60,5 +61,33 @@ struct GemmParams {
 };
 
 int launch_gemm(const GemmParams& p, int op, hipStream_t stream);
+
+// Column-streaming convolution (weights resident in registers, activations through
+// the scalar cache).  Input: bordered packed activations [B][Hp][Wp][Cw] (+ slack),
+// i.e. padding is physical.  Output is NHWC: element (n, m) at n * ldc_n + m.
+struct StreamParams {
+    const plane2* Wi;       // interleaved weights: [ceil(M/64)][Kw][64] (lane-contiguous)
+    const uint32_t* A;      // bordered packed activations as dwords (hi, lo pairs)
+    const int32_t* rowc;
+    int32_t cmul;
+    int32_t K;
+    int32_t M, Kw;
+    int32_t* C;
+    float* Cf;
+    int64_t ldc_n;
+    const float* scale;
+    const float* bias;
+    int32_t B, Hp, Wp, Ho, Wo;
+};
+
+bool stream_supported(int op, int R, int S, int Cw, int stride);
+int stream_group_size(int R, int Cw, int stride);
+int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int ranges, hipStream_t stream);
+
+// Bordered activation packing: levels NHWC [B][H][W][C] -> [B][H+2*border][W+2*border][C/32]
+// word pairs, ring pixels = border_word; `slack_pixels` more pixels of border_word follow.
+int launch_pack_bordered(const int8_t* levels, int64_t B, int64_t H, int64_t W, int64_t C, int border, int kind,
+                         plane2 border_word, int64_t slack_pixels, plane2* packed, int32_t* n_invalid,
+                         hipStream_t stream);
 
 }  // namespace fatnn

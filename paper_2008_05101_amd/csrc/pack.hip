@@ -169,6 +169,68 @@ __global__ __launch_bounds__(64) void row_constants_kernel(const plane2* __restr
     }
 }
 
+// Activations in the bordered layout: [B][H+2b][W+2b][Cw] word pairs, the ring (and
+// the slack behind the last image) filled with the word pair of the value 0, so that a
+// convolution with padding b never has to test whether a tap is inside the image.
+template <int KIND>
+__global__ __launch_bounds__(256) void pack_bordered_kernel(const int8_t* __restrict__ levels, int64_t B, int64_t H,
+                                                            int64_t W, int64_t Cw, int border, plane2 border_word,
+                                                            int64_t total, plane2* __restrict__ packed,
+                                                            int32_t* __restrict__ n_invalid) {
+    const int64_t Hp = H + 2 * border, Wp = W + 2 * border;
+    const int64_t npix = B * Hp * Wp;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += stride) {
+        const int64_t pix = id / Cw;
+        const int64_t cw = id - pix * Cw;
+        plane2 out = border_word;
+        if (pix < npix) {
+            const int64_t wp = pix % Wp;
+            const int64_t t = pix / Wp;
+            const int64_t hp = t % Hp;
+            const int64_t b = t / Hp;
+            const int64_t h = hp - border, w = wp - border;
+            if (h >= 0 && h < H && w >= 0 && w < W) {
+                // 32 levels = 32 bytes, 16-byte aligned because C is a multiple of 32
+                const uint4* s4 = reinterpret_cast<const uint4*>(levels + (((b * H + h) * W + w) * Cw + cw) * 32);
+                const uint4 a = s4[0], c = s4[1];
+                const uint32_t d[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+                uint32_t p1 = 0, p0 = 0, bad = 0;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    uint32_t q1, q0, qb;
+                    planes_of_dword<KIND>(d[k], q1, q0, qb);
+                    p1 |= q1 << (4 * k);
+                    p0 |= q0 << (4 * k);
+                    bad |= qb << (4 * k);
+                }
+                out = finish_word<KIND>(p1, p0);
+                if (bad != 0 && n_invalid != nullptr) atomicAdd(n_invalid, __popc(bad));
+            }
+        }
+        packed[id] = out;
+    }
+}
+
+// Second copy of the weight words with the 64 rows of a block contiguous per k-word.
+__global__ __launch_bounds__(256) void interleave_weights_kernel(const plane2* __restrict__ packed, int64_t rows,
+                                                                 int64_t Kw, int64_t total,
+                                                                 plane2* __restrict__ inter) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += stride) {
+        const int64_t lane = id & 63;
+        const int64_t t = id >> 6;
+        const int64_t kw = t % Kw;
+        const int64_t mb = t / Kw;
+        const int64_t row = mb * 64 + lane;
+        plane2 v;
+        v.x = 0u;
+        v.y = 0u;
+        if (row < rows) v = packed[row * Kw + kw];
+        inter[id] = v;
+    }
+}
+
 int grid_for(int64_t total, int block) {
     int64_t g = (total + block - 1) / block;
     const int64_t cap = 256 * 64;  // enough resident work for 256 CUs; the kernels stride
@@ -224,6 +286,32 @@ int launch_pack_gather(const int8_t* levels, int64_t rows, int64_t K, GatherDesc
             break;
         default: return -1;
     }
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_pack_bordered(const int8_t* levels, int64_t B, int64_t H, int64_t W, int64_t C, int border, int kind,
+                         plane2 border_word, int64_t slack_pixels, plane2* packed, int32_t* n_invalid,
+                         hipStream_t stream) {
+    const int64_t Cw = C / 32;
+    const int64_t total = (B * (H + 2 * border) * (W + 2 * border) + slack_pixels) * Cw;
+    if (total == 0) return 0;
+    dim3 grid(grid_for(total, 256)), block(256);
+    if (kind == PACK_ACT)
+        hipLaunchKernelGGL((pack_bordered_kernel<PACK_ACT>), grid, block, 0, stream, levels, B, H, W, Cw, border,
+                           border_word, total, packed, n_invalid);
+    else if (kind == PACK_TWOBIT)
+        hipLaunchKernelGGL((pack_bordered_kernel<PACK_TWOBIT>), grid, block, 0, stream, levels, B, H, W, Cw, border,
+                           border_word, total, packed, n_invalid);
+    else
+        return -1;
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_interleave_weights(const plane2* packed, int64_t rows, int64_t Kw, plane2* inter, hipStream_t stream) {
+    const int64_t total = ((rows + 63) / 64) * Kw * 64;
+    if (total == 0) return 0;
+    hipLaunchKernelGGL(interleave_weights_kernel, dim3(grid_for(total, 256)), dim3(256), 0, stream, packed, rows,
+                       Kw, total, inter);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -1,0 +1,293 @@
+// Weight-stationary, column-streaming convolution kernels for gfx950.
+//
+// Convolution layers of CNNs have few output channels (64..512), a short K per
+// output (R*S*Cin <= a few thousand) and very many columns (batch x pixels).  Here
+// a wavefront keeps the packed weights of 64 output channels in VGPRs for its whole
+// life (lane = output channel) and walks over a contiguous range of groups of U
+// neighbouring output pixels.  The activation plane words of a pixel are the same
+// for every lane, so they are fetched with scalar loads into SGPRs and enter the
+// three-input logic instruction as its scalar operand: no LDS, no barrier, and the
+// work of a wavefront can be any number of groups, which removes the tile
+// quantisation that small layers suffer on 256 CUs.
+//
+// The scalar cache serves roughly one request per 15 clocks per CU whatever the
+// request size, so the kernel reads 64-byte requests where it can and re-uses
+// every fetched input pixel for all the (output pixel, filter tap) pairs of the
+// group that touch it: an image-row strip of (U-1)*stride + R input pixels serves
+// U output pixels.  The input must be the bordered layout (physical ring of
+// value-0 pixels, slack behind the last image), so strips never need a bounds check.
+//
+// The arithmetic is the reduced form of Eq. 3 (Section 3.3): 2 logic + 2 popcount
+// instructions per 32 elements; the two-bit form of Eq. 2 needs 4 + 4.
+#include "fatnn_device.h"
+
+#include <type_traits>
+#include <utility>
+
+namespace fatnn {
+namespace {
+
+typedef const __attribute__((address_space(4))) uint32_t* sptr_t;   // scalar-loadable (constant) memory
+typedef const __attribute__((address_space(4))) char* sbytes_t;
+
+__device__ __forceinline__ void popc_acc(int32_t& acc, uint32_t x) {
+    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
+}
+
+// Wave-uniform load of NW consecutive dwords through the scalar cache (dword alignment suffices).
+template <int NW>
+__device__ __forceinline__ void sload(const sptr_t src, uint32_t* dst) {
+    typedef uint32_t vec_t __attribute__((ext_vector_type(NW)));
+    typedef const __attribute__((address_space(4))) vec_t* vptr_t;
+    const vec_t v = *reinterpret_cast<vptr_t>(src);
+#pragma unroll
+    for (int i = 0; i < NW; ++i) dst[i] = v[i];
+}
+
+// ND consecutive dwords as the fewest scalar requests (16, 8, 4, 2 dwords each).
+template <int ND, int OFF = 0>
+__device__ __forceinline__ void sload_run(const sptr_t src, uint32_t* dst) {
+    if constexpr (ND - OFF >= 16) {
+        sload<16>(src + OFF, dst + OFF);
+        sload_run<ND, OFF + 16>(src, dst);
+    } else if constexpr (ND - OFF >= 8) {
+        sload<8>(src + OFF, dst + OFF);
+        sload_run<ND, OFF + 8>(src, dst);
+    } else if constexpr (ND - OFF >= 4) {
+        sload<4>(src + OFF, dst + OFF);
+        sload_run<ND, OFF + 4>(src, dst);
+    } else if constexpr (ND - OFF >= 2) {
+        sload<2>(src + OFF, dst + OFF);
+        sload_run<ND, OFF + 2>(src, dst);
+    }
+}
+
+template <int R, int CW, int ST, int U>
+struct StreamShape {
+    static constexpr int PD = 2 * CW;                        // dwords per packed pixel
+    static constexpr int SP = (U - 1) * ST + R;              // input pixels per image-row strip
+    static constexpr int PB = (16 / PD) > 0 ? (16 / PD) : 1; // pixels per batch (one 64-byte request where possible)
+    static constexpr int CH = (SP + PB - 1) / PB;            // batches per strip
+    static constexpr int NBATCH = R * CH;                    // batches per group
+    static constexpr int BUF = PB * PD;                      // dwords per batch buffer
+};
+
+template <int OP, int R, int CW, int ST, int U>
+__global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) {
+    typedef StreamShape<R, CW, ST, U> Sh;
+    constexpr int TAPS = R * R, PD = Sh::PD, SP = Sh::SP, PB = Sh::PB, CH = Sh::CH, NBATCH = Sh::NBATCH;
+    const int lane = threadIdx.x & 63;
+    const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // blockIdx.y = group of row blocks, wave = row block inside the group; blockIdx.x = range of groups
+    const int mb = blockIdx.y * (blockDim.x >> 6) + wave_in_block;
+    if (mb * 64 >= p.M) return;
+    const int m = mb * 64 + lane;
+    const bool m_ok = m < p.M;
+
+    // ---- weights of this lane's output channel: resident for the whole kernel ----
+    plane2 w[TAPS][CW];
+    {
+        const plane2* wsrc = p.Wi + ((int64_t)mb * p.Kw) * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+            for (int c = 0; c < CW; ++c) w[t][c] = wsrc[(int64_t)(t * CW + c) * 64];
+    }
+    int32_t rc = 0;
+    float sc = 0.f, bs = 0.f;
+    if (m_ok) {
+        if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
+        if (p.Cf != nullptr) {
+            sc = p.scale[m];
+            if (p.bias != nullptr) bs = p.bias[m];
+        }
+    }
+
+    // ---- this wavefront's range of groups; a group = U neighbouring pixels of one output row ----
+    const int wgroups = (p.Wo + U - 1) / U;
+    const int64_t ngroups = (int64_t)p.B * p.Ho * wgroups;
+    const int nranges = gridDim.x;
+    const int range = blockIdx.x;
+    const int g_begin = (int)(((int64_t)range * ngroups) / nranges);
+    const int g_end = (int)(((int64_t)(range + 1) * ngroups) / nranges);
+    if (g_begin >= g_end) return;
+
+    int wg = g_begin % wgroups;
+    int t0 = g_begin / wgroups;
+    int ho = t0 % p.Ho;
+    int b = t0 / p.Ho;
+
+    const sbytes_t xbase = (sbytes_t)(uintptr_t)p.A;
+    constexpr uint32_t kPixBytes = CW * 8u;
+    const uint32_t row_bytes = (uint32_t)p.Wp * kPixBytes;     // bordered row; the tensor is < 4 GiB (host check)
+    const uint32_t img_bytes = (uint32_t)p.Hp * row_bytes;
+
+    // byte offset of the first input pixel of the current group's first strip (bordered coordinates)
+    auto strip_offset = [&]() {
+        return (uint32_t)b * img_bytes + (uint32_t)(ho * ST) * row_bytes + (uint32_t)(wg * U * ST) * kPixBytes;
+    };
+    auto advance = [&]() {
+        if (++wg == wgroups) {
+            wg = 0;
+            if (++ho == p.Ho) {
+                ho = 0;
+                ++b;
+            }
+        }
+    };
+    // batch i of a group = pixels [c*PB, c*PB+np) of the strip of filter row r
+    auto issue = [&](auto i_tag, uint32_t goff, uint32_t* dst) {
+        constexpr int i = decltype(i_tag)::value;
+        constexpr int r = i / CH, c = i % CH;
+        constexpr int np = (SP - c * PB) < PB ? (SP - c * PB) : PB;
+        const sptr_t src = (sptr_t)(xbase + (goff + (uint32_t)r * row_bytes + (uint32_t)(c * PB) * kPixBytes));
+        sload_run<np * PD>(src, dst);
+    };
+
+    int32_t acc[U];
+    auto consume = [&](auto i_tag, const uint32_t* x) {
+        constexpr int i = decltype(i_tag)::value;
+        constexpr int r = i / CH, c = i % CH;
+        constexpr int np = (SP - c * PB) < PB ? (SP - c * PB) : PB;
+#pragma unroll
+        for (int j = 0; j < np; ++j) {
+            const int jj = c * PB + j;   // position in the strip
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int s = jj - u * ST;   // filter column of this pixel for output pixel u
+                if (s < 0 || s >= R) continue;
+#pragma unroll
+                for (int cw = 0; cw < CW; ++cw) {
+                    const plane2 ww = w[r * R + s][cw];
+                    const uint32_t xh = x[j * PD + 2 * cw], xl = x[j * PD + 2 * cw + 1];
+                    if (OP == OP_TERNARY) {
+                        popc_acc(acc[u], (xh ^ ww.x) & ww.y);
+                        popc_acc(acc[u], (xl ^ ww.x) & ww.y);
+                    } else {
+                        popc_acc(acc[u], xh ^ ww.x);
+                        popc_acc(acc[u], xh ^ ww.y);
+                        popc_acc(acc[u], xl ^ ww.x);
+                        popc_acc(acc[u], xl ^ ww.y);
+                    }
+                }
+            }
+        }
+    };
+
+    uint32_t buf[2][Sh::BUF];
+    uint32_t goff = strip_offset();
+    issue(std::integral_constant<int, 0>{}, goff, buf[0]);
+
+    // One group: batch i+1 (or batch 0 of the next group) is in flight while batch i is
+    // consumed.  A scalar-load wait waits for every outstanding load, so the wait for batch
+    // i comes BEFORE batch i+1 is issued.  PAR = which buffer holds batch 0.
+    auto run_group = [&](auto par_tag, int g) {
+        constexpr int PAR = decltype(par_tag)::value;
+        const int wo0 = wg * U;
+        const int64_t n0 = ((int64_t)b * p.Ho + ho) * p.Wo + wo0;
+        uint32_t goff_next = goff;
+        if (g + 1 < g_end) {
+            advance();
+            goff_next = strip_offset();
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = 0;
+        auto step = [&](auto i_tag) {
+            constexpr int i = decltype(i_tag)::value;
+            __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (i + 1 < NBATCH)
+                issue(std::integral_constant<int, i + 1>{}, goff, buf[(PAR + i + 1) & 1]);
+            else
+                issue(std::integral_constant<int, 0>{}, goff_next, buf[(PAR + i + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(i_tag, buf[(PAR + i) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        [&]<int... I>(std::integer_sequence<int, I...>) { (step(std::integral_constant<int, I>{}), ...); }
+        (std::make_integer_sequence<int, NBATCH>{});
+        goff = goff_next;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (wo0 + u < p.Wo && m_ok) {
+                const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : p.K - (acc[u] >> 1);
+                const int64_t o = (n0 + u) * p.ldc_n + m;
+                if (p.C != nullptr) p.C[o] = v;
+                if (p.Cf != nullptr) {
+                    float f = sc * (float)v;
+                    if (p.bias != nullptr) f = f + bs;
+                    p.Cf[o] = f;
+                }
+            }
+        }
+    };
+
+    int g = g_begin;
+    while (g < g_end) {
+        run_group(std::integral_constant<int, 0>{}, g);
+        ++g;
+        if constexpr ((NBATCH & 1) != 0) {
+            // an odd number of batches leaves the prefetched batch in the other buffer
+            if (g < g_end) {
+                run_group(std::integral_constant<int, 1>{}, g);
+                ++g;
+            } else {
+                break;
+            }
+        }
+    }
+}
+
+template <int OP, int R, int CW, int ST, int U>
+int launch_inst(const StreamParams& p, int ranges, hipStream_t stream) {
+    const int mblocks = (p.M + 63) / 64;
+    const int wpb = mblocks < 4 ? mblocks : 4;
+    dim3 grid((unsigned)ranges, (unsigned)((mblocks + wpb - 1) / wpb));
+    hipLaunchKernelGGL((stream_conv_kernel<OP, R, CW, ST, U>), grid, dim3(64 * wpb), 0, stream, p);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Output pixels per group for a filter size / channel-word count / stride.
+constexpr int group_u(int R, int CW, int ST) {
+    if (R == 3) return (ST == 1) ? (CW == 2 ? 6 : 4) : (CW == 8 ? 2 : 4);
+    return (CW >= 8) ? 4 : (CW == 4 ? 4 : 8);   // 1x1
+}
+
+}  // namespace
+
+int stream_group_size(int R, int Cw, int stride) { return group_u(R, Cw, stride); }
+
+bool stream_supported(int op, int R, int S, int Cw, int stride) {
+    if (op != OP_TERNARY && op != OP_TWOBIT_TERNARY) return false;
+    if (R != S || (stride != 1 && stride != 2)) return false;
+    if (R == 3) return Cw == 2 || Cw == 4 || Cw == 8;
+    if (R == 1) return Cw == 2 || Cw == 4 || Cw == 8 || Cw == 16;
+    return false;
+}
+
+int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int ranges, hipStream_t stream) {
+#define FATNN_STREAM_CASE(RR, CC, SS)                                                                          \
+    if (R == RR && Cw == CC && stride == SS) {                                                                 \
+        constexpr int UU = group_u(RR, CC, SS);                                                                \
+        return op == OP_TERNARY ? launch_inst<OP_TERNARY, RR, CC, SS, UU>(p, ranges, stream)                   \
+                                : launch_inst<OP_TWOBIT_TERNARY, RR, CC, SS, UU>(p, ranges, stream);           \
+    }
+    FATNN_STREAM_CASE(3, 2, 1)
+    FATNN_STREAM_CASE(3, 4, 1)
+    FATNN_STREAM_CASE(3, 8, 1)
+    FATNN_STREAM_CASE(3, 2, 2)
+    FATNN_STREAM_CASE(3, 4, 2)
+    FATNN_STREAM_CASE(3, 8, 2)
+    FATNN_STREAM_CASE(1, 2, 1)
+    FATNN_STREAM_CASE(1, 4, 1)
+    FATNN_STREAM_CASE(1, 8, 1)
+    FATNN_STREAM_CASE(1, 16, 1)
+    FATNN_STREAM_CASE(1, 2, 2)
+    FATNN_STREAM_CASE(1, 4, 2)
+    FATNN_STREAM_CASE(1, 8, 2)
+    FATNN_STREAM_CASE(1, 16, 2)
+#undef FATNN_STREAM_CASE
+    return -3;
+}
+
+}  // namespace fatnn

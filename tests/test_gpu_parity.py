@@ -44,10 +44,16 @@ def gemm_gpu(Lw, La, mode, **kw):
     return fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, **kw)
 
 
-def conv_gpu(Lw, Lx, stride, pad, mode, **kw):
+def conv_gpu(Lw, Lx, stride, pad, mode, bordered=True, **kw):
+    """bordered=True: activations packed with a physical ring of value-0 pixels (streaming
+    kernel where the shape allows); False: plain pixel order (tiled implicit-GEMM kernel)."""
     Cout, R, S, Cin = Lw.shape
     B, H, W, _ = Lx.shape
     Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT, fatnn.OHWI)
+    if bordered:
+        Xp = fatnn.pack_ternary_bordered(dev(Lx), pad, mode)
+        return fatnn.ternary_conv2d(Wp, Xp, B, Cin, H, W, Cout, R, S, stride, pad, mode,
+                                    x_layout=fatnn.X_BORDERED, **kw)
     Xp = fatnn.pack_ternary(dev(Lx), fatnn.ACT, fatnn.NHWC)
     return fatnn.ternary_conv2d(Wp, Xp, B, Cin, H, W, Cout, R, S, stride, pad, mode, **kw)
 
@@ -200,15 +206,39 @@ def test_gemm_scale_epilogue():
 @pytest.mark.parametrize("Cin,Cout,H,W,R,stride,pad", [
     (32, 5, 6, 7, 3, 1, 1), (64, 64, 9, 9, 3, 1, 1), (64, 70, 12, 10, 3, 2, 1), (96, 33, 8, 8, 3, 1, 1),
     (64, 128, 14, 14, 1, 2, 0), (256, 64, 7, 9, 1, 1, 0), (32, 16, 5, 5, 3, 1, 0), (128, 130, 7, 7, 3, 1, 1),
+    (256, 200, 9, 6, 3, 2, 1), (512, 64, 5, 5, 3, 1, 1), (512, 300, 6, 6, 1, 1, 0), (128, 1, 4, 4, 3, 1, 1),
+    (64, 64, 1, 1, 1, 1, 0), (64, 64, 2, 1, 3, 1, 1), (128, 64, 30, 3, 3, 2, 1),
 ])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_conv_parity_small(Cin, Cout, H, W, R, stride, pad, mode):
+@pytest.mark.parametrize("bordered", [True, False])
+def test_conv_parity_small(Cin, Cout, H, W, R, stride, pad, mode, bordered):
     rnd = np.random.default_rng(Cin + Cout + H + R + stride + mode)
     B = 3
     Lw = rnd.integers(0, 3, size=(Cout, R, R, Cin), dtype=np.int8)
     Lx = rnd.integers(0, 3, size=(B, H, W, Cin), dtype=np.int8)
-    Y, _ = conv_gpu(Lw, Lx, stride, pad, mode)
+    Y, _ = conv_gpu(Lw, Lx, stride, pad, mode, bordered=bordered)
     assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, mode))
+
+
+def test_bordered_pack_layout():
+    rnd = np.random.default_rng(77)
+    B, H, W, C = 2, 5, 4, 64
+    Lx = rnd.integers(0, 3, size=(B, H, W, C), dtype=np.int8)
+    plain = fatnn.pack_ternary(dev(Lx), fatnn.ACT, fatnn.NHWC).cpu().numpy().view(np.uint32).reshape(B, H, W, 2, 2)
+    for mode, ring in ((0, (0, 0xFFFFFFFF)), (1, (0, 0))):
+        buf = fatnn.pack_ternary_bordered(dev(Lx), 1, mode)
+        assert buf.numel() == fatnn.bordered_act_bytes(B, H, W, C, 1)
+        words = buf.cpu().numpy().view(np.uint32)
+        body = words[: B * (H + 2) * (W + 2) * 4].reshape(B, H + 2, W + 2, 2, 2)
+        assert np.array_equal(body[:, 1:-1, 1:-1], plain)
+        mask = np.ones((H + 2, W + 2), bool)
+        mask[1:-1, 1:-1] = False
+        assert (body[:, mask][..., 0] == ring[0]).all() and (body[:, mask][..., 1] == ring[1]).all()
+        slack = words[B * (H + 2) * (W + 2) * 4:].reshape(-1, 2)
+        assert slack.shape[0] == 64 * 2 and (slack[:, 0] == ring[0]).all() and (slack[:, 1] == ring[1]).all()
+    # border 0 = plain order plus slack
+    b0 = fatnn.pack_ternary_bordered(dev(Lx), 0, 0).cpu().numpy().view(np.uint32)
+    assert np.array_equal(b0[: plain.size], plain.reshape(-1))
 
 
 def test_conv_cfg2_full_with_scale_epilogue():
@@ -223,13 +253,16 @@ def test_conv_cfg2_full_with_scale_epilogue():
     assert np.array_equal(Yf.cpu().numpy(), wantf)
     Ys, _ = conv_gpu(Lw, Lx, 1, 1, fatnn.SYM)
     assert np.array_equal(Ys.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, 1, 1, 0))
+    Yt, Ytf = conv_gpu(Lw, Lx, 1, 1, case.act_mode, bordered=False, scale=dev(scale), bias=dev(bias))
+    assert np.array_equal(Yt.cpu().numpy(), want) and np.array_equal(Ytf.cpu().numpy(), wantf)
 
 
 @pytest.mark.parametrize("layer", range(19))
-def test_conv_cfg3_layers_batch4(layer):
+@pytest.mark.parametrize("bordered", [True, False])
+def test_conv_cfg3_layers_batch4(layer, bordered):
     case = si.cfg3(batch=4)[layer]
     Lw, Lx = case.make()
-    Y, _ = conv_gpu(Lw, Lx, case.stride, case.pad, case.act_mode)
+    Y, _ = conv_gpu(Lw, Lx, case.stride, case.pad, case.act_mode, bordered=bordered)
     assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode))
 
 
@@ -321,13 +354,16 @@ def test_twobit_on_ternary_data_equals_ternary_path():
     assert np.array_equal(C2.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
 
 
-@pytest.mark.parametrize("R,stride,pad", [(3, 1, 1), (3, 2, 1), (1, 1, 0)])
-def test_twobit_conv_parity(R, stride, pad):
-    rnd = np.random.default_rng(R + stride)
-    Lw = rnd.integers(0, 3, size=(70, R, R, 64), dtype=np.int8)
-    Lx = rnd.integers(0, 3, size=(3, 10, 9, 64), dtype=np.int8)
+@pytest.mark.parametrize("R,stride,pad,Cin", [(3, 1, 1, 64), (3, 2, 1, 64), (1, 1, 0, 64), (3, 1, 1, 96), (3, 1, 1, 256)])
+def test_twobit_conv_parity(R, stride, pad, Cin):
+    rnd = np.random.default_rng(R + stride + Cin)
+    Lw = rnd.integers(0, 3, size=(70, R, R, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(3, 10, 9, Cin), dtype=np.int8)
     code = np.array([0, 1, 3], dtype=np.int8)
-    Wp = fatnn.pack_twobit(dev(code[Lw]), fatnn.OHWI)
-    Xp = fatnn.pack_twobit(dev(code[Lx]), fatnn.NHWC)
-    Y = fatnn.twobit_conv2d(Wp, Xp, 3, 64, 10, 9, 70, R, R, stride, pad)
+    Wp = fatnn.pack_twobit(dev(code[Lw]), fatnn.WEIGHT, fatnn.OHWI)
+    Xp = fatnn.pack_twobit(dev(code[Lx]), fatnn.ACT, fatnn.NHWC)
+    Y = fatnn.twobit_conv2d(Wp, Xp, 3, Cin, 10, 9, 70, R, R, stride, pad)
     assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, 0))
+    Xb = fatnn.pack_twobit_bordered(dev(code[Lx]), pad)
+    Yb = fatnn.twobit_conv2d(Wp, Xb, 3, Cin, 10, 9, 70, R, R, stride, pad, x_layout=fatnn.X_BORDERED)
+    assert torch.equal(Y, Yb)
