@@ -32,6 +32,10 @@ TERNARY_OPS_PER_LANE_INSTR = 64 / 4
 TWOBIT_OPS_PER_LANE_INSTR = 64 / 8
 TERNARY_PEAK_TOPS = VALU_LANE_OPS_PER_S * TERNARY_OPS_PER_LANE_INSTR / 1e12     # 629.1
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script, scaled by the same counters' readings for a plain copy of known size (profiles/*.md give the
+# commands, the raw readings and the scale factors 2.000 / 1.000).
+MEASURED_TRAFFIC_BYTES = {"cfg2": int((3096.1 * 2.000 + 25088.0 * 1.000) * 1024), "cfg4": None}
 
 
 def parse_args():
@@ -42,6 +46,9 @@ def parse_args():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 256 MiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE "
+                         "counters of a rocprofv3 --pmc run) and exit")
     return ap.parse_args()
 
 
@@ -105,6 +112,15 @@ def main():
     fatnn.lib()   # fail loudly now if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 device copies of 268435456 bytes (read 256 MiB + write 256 MiB each)"}))
+        return
 
     extra = {}
     if args.workload == "cfg2":
@@ -183,7 +199,7 @@ def main():
     achieved = ops_per_step / (kernel_ms * 1e-3) / 1e12
     roofline = {"bound": "alu", "kernel": dominant, "achieved": round(achieved, 2),
                 "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s", "frac": round(achieved / TERNARY_PEAK_TOPS, 4),
-                "traffic": None, "kernel_ms": round(kernel_ms, 5),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel_ms": round(kernel_ms, 5),
                 "peak_basis": "256 CU x 64 lanes x 2.4 GHz = 39.3 T lane-instr/s; 4 lane-instr per 64 ops"}
 
     # ---- side measurements (outside the timed region) ---------------------------------------

@@ -21,6 +21,7 @@
 // instructions per 32 elements; the two-bit form of Eq. 2 needs 4 + 4.
 #include "fatnn_device.h"
 
+#include <stdlib.h>
 #include <type_traits>
 #include <utility>
 
@@ -212,11 +213,12 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
             if (wo0 + u < p.Wo && m_ok) {
                 const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : p.K - (acc[u] >> 1);
                 const int64_t o = (n0 + u) * p.ldc_n + m;
-                if (p.C != nullptr) p.C[o] = v;
+                // outputs are written once and not read again by this kernel: stream them out
+                if (p.C != nullptr) __builtin_nontemporal_store(v, &p.C[o]);
                 if (p.Cf != nullptr) {
                     float f = sc * (float)v;
                     if (p.bias != nullptr) f = f + bs;
-                    p.Cf[o] = f;
+                    __builtin_nontemporal_store(f, &p.Cf[o]);
                 }
             }
         }
@@ -243,7 +245,15 @@ int launch_inst(const StreamParams& p, int ranges, hipStream_t stream) {
     const int mblocks = (p.M + 63) / 64;
     const int wpb = mblocks < 4 ? mblocks : 4;
     dim3 grid((unsigned)ranges, (unsigned)((mblocks + wpb - 1) / wpb));
-    hipLaunchKernelGGL((stream_conv_kernel<OP, R, CW, ST, U>), grid, dim3(64 * wpb), 0, stream, p);
+    // The kernel uses no LDS.  Asking for a slice of it anyway caps how many workgroups the
+    // dispatcher can stack on one CU, which spreads a grid that fits the chip in one round
+    // evenly over the 256 CUs instead of filling some CUs to their occupancy limit.
+    const int64_t total_wgs = (int64_t)grid.x * grid.y;
+    const int64_t per_cu = (total_wgs + 255) / 256;
+    int64_t lds = per_cu > 0 ? ((160 * 1024) / per_cu) & ~1023LL : 0;
+    if (lds > 64 * 1024) lds = 64 * 1024;
+    if (per_cu > 32 || getenv("FATNN_STREAM_NO_LDS_CAP") != nullptr) lds = 0;
+    hipLaunchKernelGGL((stream_conv_kernel<OP, R, CW, ST, U>), grid, dim3(64 * wpb), (size_t)lds, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
