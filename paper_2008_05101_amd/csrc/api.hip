@@ -173,9 +173,9 @@ bool want_stream(int op, int R, int S, int Cw, int stride) {
 // Number of ranges of pixel groups (= wavefronts per block of 64 output channels).  All
 // wavefronts are meant to be resident at once, the same number on every SIMD, and
 // each should see enough groups to amortise loading its weights.
-int stream_ranges(int64_t M, int64_t ngroups, int64_t group_size, int64_t Kw) {
+int stream_ranges(int64_t M, int64_t ngroups, int64_t group_size, int64_t Kw, int64_t max_groups_per_range) {
     const int64_t mblocks = (M + 63) / 64;
-    const int64_t vgprs = 2 * Kw + 24;
+    const int64_t vgprs = 2 * (Kw > 72 ? 72 : Kw) + 24;
     int64_t occ = 512 / vgprs;
     if (occ > 8) occ = 8;
     if (occ < 1) occ = 1;
@@ -186,6 +186,8 @@ int stream_ranges(int64_t M, int64_t ngroups, int64_t group_size, int64_t Kw) {
     if (wps < 1) wps = 1;
     int64_t ranges = (1024 * wps) / mblocks;
     if (ranges < 1) ranges = 1;
+    const int64_t need = (ngroups + max_groups_per_range - 1) / max_groups_per_range;
+    if (ranges < need) ranges = need;
     if (ranges > ngroups) ranges = ngroups;
     return (int)ranges;
 }
@@ -220,7 +222,7 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
         q.B = (int32_t)B; q.Hp = (int32_t)Hs; q.Wp = (int32_t)Ws; q.Ho = (int32_t)cs.Ho; q.Wo = (int32_t)cs.Wo;
         const int U = stream_group_size(R, Cw, stride);
         const int64_t ngroups = B * cs.Ho * ((cs.Wo + U - 1) / U);
-        const int ranges = stream_ranges(Cout, ngroups, U, q.Kw);
+        const int ranges = stream_ranges(Cout, ngroups, U, q.Kw, stream_max_groups_per_range(R, Cw, stride));
         return launch_stream_conv(q, op, R, Cw, stride, ranges, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
     }
     GemmParams p{};

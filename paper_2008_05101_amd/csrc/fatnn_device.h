@@ -82,6 +82,7 @@ struct StreamParams {
 
 bool stream_supported(int op, int R, int S, int Cw, int stride);
 int stream_group_size(int R, int Cw, int stride);
+int stream_max_groups_per_range(int R, int Cw, int stride);
 int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int ranges, hipStream_t stream);
 
 // Bordered activation packing: levels NHWC [B][H][W][C] -> [B][H+2*border][W+2*border][C/32]

@@ -63,6 +63,7 @@ __device__ __forceinline__ void sload_run(const sptr_t src, uint32_t* dst) {
     }
 }
 
+// CW = channel words resident per pass, CWT = channel words per stored pixel (CWT = CW * passes).
 template <int R, int CW, int ST, int U>
 struct StreamShape {
     static constexpr int PD = 2 * CW;                        // dwords per packed pixel
@@ -73,10 +74,18 @@ struct StreamShape {
     static constexpr int BUF = PB * PD;                      // dwords per batch buffer
 };
 
-template <int OP, int R, int CW, int ST, int U>
+// Columns whose partial sums a wavefront may keep in LDS between two passes over K.
+constexpr int kPassCols = 64;
+
+template <int OP, int R, int CW, int CWT, int ST, int U>
 __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) {
     typedef StreamShape<R, CW, ST, U> Sh;
     constexpr int TAPS = R * R, PD = Sh::PD, SP = Sh::SP, PB = Sh::PB, CH = Sh::CH, NBATCH = Sh::NBATCH;
+    constexpr int NPASS = CWT / CW;
+    static_assert(CWT % CW == 0, "passes must tile the channel words");
+    // Partial sums between passes (only when K does not fit the register file in one pass):
+    // [wave][column of the range][lane], private to the wavefront, so no barrier is needed.
+    extern __shared__ int32_t pass_partials[];
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // blockIdx.y = group of row blocks, wave = row block inside the group; blockIdx.x = range of groups
@@ -85,15 +94,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     const int m = mb * 64 + lane;
     const bool m_ok = m < p.M;
 
-    // ---- weights of this lane's output channel: resident for the whole kernel ----
-    plane2 w[TAPS][CW];
-    {
-        const plane2* wsrc = p.Wi + ((int64_t)mb * p.Kw) * 64 + lane;
-#pragma unroll
-        for (int t = 0; t < TAPS; ++t)
-#pragma unroll
-            for (int c = 0; c < CW; ++c) w[t][c] = wsrc[(int64_t)(t * CW + c) * 64];
-    }
+    plane2 w[TAPS][CW];   // weights of this lane's output channel for the current pass
+    const plane2* wsrc = p.Wi + ((int64_t)mb * p.Kw) * 64 + lane;
     int32_t rc = 0;
     float sc = 0.f, bs = 0.f;
     if (m_ok) {
@@ -113,13 +115,11 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     const int g_end = (int)(((int64_t)(range + 1) * ngroups) / nranges);
     if (g_begin >= g_end) return;
 
-    int wg = g_begin % wgroups;
-    int t0 = g_begin / wgroups;
-    int ho = t0 % p.Ho;
-    int b = t0 / p.Ho;
+    int wg, ho, b;
+    int32_t* const my_partials = pass_partials + (size_t)wave_in_block * kPassCols * 64 + lane;
 
-    const sbytes_t xbase = (sbytes_t)(uintptr_t)p.A;
-    constexpr uint32_t kPixBytes = CW * 8u;
+    sbytes_t xbase = (sbytes_t)(uintptr_t)p.A;
+    constexpr uint32_t kPixBytes = CWT * 8u;
     const uint32_t row_bytes = (uint32_t)p.Wp * kPixBytes;     // bordered row; the tensor is < 4 GiB (host check)
     const uint32_t img_bytes = (uint32_t)p.Hp * row_bytes;
 
@@ -176,8 +176,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     };
 
     uint32_t buf[2][Sh::BUF];
-    uint32_t goff = strip_offset();
-    issue(std::integral_constant<int, 0>{}, goff, buf[0]);
+    uint32_t goff = 0;
+    int pass = 0;
 
     // One group: batch i+1 (or batch 0 of the next group) is in flight while batch i is
     // consumed.  A scalar-load wait waits for every outstanding load, so the wait for batch
@@ -191,8 +191,12 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
             advance();
             goff_next = strip_offset();
         }
+        const int col_local = (g - g_begin) * U;
 #pragma unroll
-        for (int u = 0; u < U; ++u) acc[u] = 0;
+        for (int u = 0; u < U; ++u) {
+            acc[u] = 0;
+            if (NPASS > 1 && pass > 0) acc[u] = my_partials[(col_local + u) * 64];
+        }
         auto step = [&](auto i_tag) {
             constexpr int i = decltype(i_tag)::value;
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
@@ -208,6 +212,11 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         [&]<int... I>(std::integer_sequence<int, I...>) { (step(std::integral_constant<int, I>{}), ...); }
         (std::make_integer_sequence<int, NBATCH>{});
         goff = goff_next;
+        if (NPASS > 1 && pass + 1 < NPASS) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) my_partials[(col_local + u) * 64] = acc[u];
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (wo0 + u < p.Wo && m_ok) {
@@ -224,53 +233,69 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         }
     };
 
-    int g = g_begin;
-    while (g < g_end) {
-        run_group(std::integral_constant<int, 0>{}, g);
-        ++g;
-        if constexpr ((NBATCH & 1) != 0) {
-            // an odd number of batches leaves the prefetched batch in the other buffer
-            if (g < g_end) {
-                run_group(std::integral_constant<int, 1>{}, g);
-                ++g;
-            } else {
-                break;
+    for (pass = 0; pass < NPASS; ++pass) {
+        // this pass's slice of the channel words: weights into registers, activations by offset
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+            for (int c = 0; c < CW; ++c) w[t][c] = wsrc[(int64_t)(t * CWT + pass * CW + c) * 64];
+        xbase = (sbytes_t)(uintptr_t)p.A + (uint32_t)pass * (CW * 8u);
+        wg = g_begin % wgroups;
+        const int t0 = g_begin / wgroups;
+        ho = t0 % p.Ho;
+        b = t0 / p.Ho;
+        goff = strip_offset();
+        issue(std::integral_constant<int, 0>{}, goff, buf[0]);
+
+        int g = g_begin;
+        while (g < g_end) {
+            run_group(std::integral_constant<int, 0>{}, g);
+            ++g;
+            if constexpr ((NBATCH & 1) != 0) {
+                // an odd number of batches leaves the prefetched batch in the other buffer
+                if (g < g_end) {
+                    run_group(std::integral_constant<int, 1>{}, g);
+                    ++g;
+                } else {
+                    break;
+                }
             }
         }
     }
 }
 
-template <int OP, int R, int CW, int ST, int U>
+template <int OP, int R, int CW, int CWT, int ST, int U>
 int launch_inst(const StreamParams& p, int ranges, hipStream_t stream) {
     const int mblocks = (p.M + 63) / 64;
     const int wpb = mblocks < 4 ? mblocks : 4;
     dim3 grid((unsigned)ranges, (unsigned)((mblocks + wpb - 1) / wpb));
-    // The kernel uses no LDS.  Asking for a slice of it anyway caps how many workgroups the
-    // dispatcher can stack on one CU, which spreads a grid that fits the chip in one round
-    // evenly over the 256 CUs instead of filling some CUs to their occupancy limit.
-    const int64_t total_wgs = (int64_t)grid.x * grid.y;
-    const int64_t per_cu = (total_wgs + 255) / 256;
-    int64_t lds = per_cu > 0 ? ((160 * 1024) / per_cu) & ~1023LL : 0;
-    if (lds > 64 * 1024) lds = 64 * 1024;
-    if (per_cu > 32 || getenv("FATNN_STREAM_NO_LDS_CAP") != nullptr) lds = 0;
-    hipLaunchKernelGGL((stream_conv_kernel<OP, R, CW, ST, U>), grid, dim3(64 * wpb), (size_t)lds, stream, p);
+    const size_t lds = (CWT > CW) ? (size_t)wpb * kPassCols * 64 * sizeof(int32_t) : 0;
+    hipLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U>), grid, dim3(64 * wpb), lds, stream, p);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 // Output pixels per group for a filter size / channel-word count / stride.
 constexpr int group_u(int R, int CW, int ST) {
-    if (R == 3) return (ST == 1) ? (CW == 2 ? 6 : 4) : (CW == 8 ? 2 : 4);
+    if (R == 3) return (ST == 1) ? (CW == 2 ? 6 : 4) : (CW >= 8 ? 2 : 4);
     return (CW >= 8) ? 4 : (CW == 4 ? 4 : 8);   // 1x1
 }
+// Channel words kept in registers per pass: everything, except for 3x3 filters over 512 channels.
+constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : CWT; }
 
 }  // namespace
 
 int stream_group_size(int R, int Cw, int stride) { return group_u(R, Cw, stride); }
 
+// Largest number of pixel groups one wavefront may own (bounded only for multi-pass shapes).
+int stream_max_groups_per_range(int R, int Cw, int stride) {
+    if (resident_cw(R, Cw) == Cw) return 0x7FFFFFFF;
+    return kPassCols / group_u(R, Cw, stride);
+}
+
 bool stream_supported(int op, int R, int S, int Cw, int stride) {
     if (op != OP_TERNARY && op != OP_TWOBIT_TERNARY) return false;
     if (R != S || (stride != 1 && stride != 2)) return false;
-    if (R == 3) return Cw == 2 || Cw == 4 || Cw == 8;
+    if (R == 3) return Cw == 2 || Cw == 4 || Cw == 8 || Cw == 16;
     if (R == 1) return Cw == 2 || Cw == 4 || Cw == 8 || Cw == 16;
     return false;
 }
@@ -279,12 +304,15 @@ int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride,
 #define FATNN_STREAM_CASE(RR, CC, SS)                                                                          \
     if (R == RR && Cw == CC && stride == SS) {                                                                 \
         constexpr int UU = group_u(RR, CC, SS);                                                                \
-        return op == OP_TERNARY ? launch_inst<OP_TERNARY, RR, CC, SS, UU>(p, ranges, stream)                   \
-                                : launch_inst<OP_TWOBIT_TERNARY, RR, CC, SS, UU>(p, ranges, stream);           \
+        constexpr int RC = resident_cw(RR, CC);                                                                \
+        return op == OP_TERNARY ? launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream)               \
+                                : launch_inst<OP_TWOBIT_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream);       \
     }
     FATNN_STREAM_CASE(3, 2, 1)
     FATNN_STREAM_CASE(3, 4, 1)
     FATNN_STREAM_CASE(3, 8, 1)
+    FATNN_STREAM_CASE(3, 16, 1)
+    FATNN_STREAM_CASE(3, 16, 2)
     FATNN_STREAM_CASE(3, 2, 2)
     FATNN_STREAM_CASE(3, 4, 2)
     FATNN_STREAM_CASE(3, 8, 2)
