@@ -180,6 +180,17 @@ int fatnn_twobit_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B,
                         int64_t W, int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t *Y,
                         void *stream);
 
+/*
+ * Measurement hook (no paper passage: it serves the roofline report).  The next
+ * fatnn_*_gemm / fatnn_*_conv2d call made by the calling thread attaches the two
+ * events to its kernel dispatch, so that hipEventElapsedTime(start, stop) is the
+ * duration of that kernel alone, without the launch gap that events recorded around
+ * the call would include.  Both are hipEvent_t created by the caller with timing
+ * enabled; they stay the caller's.  The hook is consumed by that one launch;
+ * (NULL, NULL) clears it.  Giving only one event returns FATNN_ERR_NULL.
+ */
+int fatnn_time_next_launch(void *start_event, void *stop_event);
+
 const char *fatnn_status_str(int status);
 int fatnn_version(void);
 

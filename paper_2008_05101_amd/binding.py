@@ -23,7 +23,7 @@ EXPORTS = [
     "fatnn_weight_interleaved_offset", "fatnn_pack_ternary", "fatnn_bordered_act_bytes",
     "fatnn_pack_ternary_bordered", "fatnn_pack_twobit_bordered",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
-    "fatnn_twobit_conv2d", "fatnn_status_str", "fatnn_version",
+    "fatnn_twobit_conv2d", "fatnn_time_next_launch", "fatnn_status_str", "fatnn_version",
 ]
 
 
@@ -66,6 +66,7 @@ def lib() -> ctypes.CDLL:
         l.fatnn_pack_twobit_bordered.argtypes = [vp, dims4, i32, vp, sz, vp, vp]
         l.fatnn_twobit_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp]
         l.fatnn_twobit_conv2d.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
+        l.fatnn_time_next_launch.argtypes = [vp, vp]
         l.fatnn_status_str.argtypes = [i32]
         l.fatnn_status_str.restype = ctypes.c_char_p
         l.fatnn_version.restype = i32
@@ -98,6 +99,11 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
     if not t.is_contiguous():
         raise ValueError(f"{what} must be contiguous")
     return t
+
+
+def time_next_launch(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """fatnn_time_next_launch: raw hipEvent_t handles (ints) or (None, None)."""
+    _check(lib().fatnn_time_next_launch(start_event, stop_event), "fatnn_time_next_launch")
 
 
 def words_per_row(K: int) -> int:

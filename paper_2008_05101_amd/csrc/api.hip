@@ -8,6 +8,18 @@
 
 using namespace fatnn;
 
+namespace fatnn {
+namespace {
+thread_local LaunchTiming g_timing = {nullptr, nullptr};
+}
+LaunchTiming take_launch_timing() {
+    const LaunchTiming t = g_timing;
+    g_timing.start = nullptr;
+    g_timing.stop = nullptr;
+    return t;
+}
+}  // namespace fatnn
+
 namespace {
 
 constexpr int64_t kMaxRows = 0x7FFFFFFFLL;
@@ -413,6 +425,13 @@ int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B,
     if (!aligned(Wp, 16) || !aligned(Xp, 16) || !aligned(Y, 4)) return FATNN_ERR_ALIGN;
     return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TWOBIT_TERNARY, FATNN_SYM, Y,
                     nullptr, nullptr, nullptr, stream);
+}
+
+int fatnn_time_next_launch(void* start_event, void* stop_event) {
+    if ((start_event == nullptr) != (stop_event == nullptr)) return FATNN_ERR_NULL;
+    fatnn::g_timing.start = reinterpret_cast<hipEvent_t>(start_event);
+    fatnn::g_timing.stop = reinterpret_cast<hipEvent_t>(stop_event);
+    return FATNN_OK;
 }
 
 const char* fatnn_status_str(int status) {

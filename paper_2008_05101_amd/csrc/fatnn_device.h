@@ -2,6 +2,7 @@
 // gfx950 only.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -61,6 +62,13 @@ struct GemmParams {
 };
 
 int launch_gemm(const GemmParams& p, int op, hipStream_t stream);
+
+// Measurement hook (fatnn_time_next_launch): events that the next GEMM / convolution
+// kernel launch of this thread attaches to the dispatch itself; consumed by that launch.
+struct LaunchTiming {
+    hipEvent_t start, stop;
+};
+LaunchTiming take_launch_timing();
 
 // Column-streaming convolution (weights resident in registers, activations through
 // the scalar cache).  Input: bordered packed activations [B][Hp][Wp][Cw] (+ slack),

@@ -324,12 +324,13 @@ int launch_shape(const GemmParams& p, hipStream_t stream) {
     const int64_t ntiles = (int64_t)tiles_m * tiles_n;
     if (ntiles > 0x7FFFFFF0LL) return -2;
     const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
+    const LaunchTiming t = take_launch_timing();
     if (p.is_conv)
-        hipLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true>), dim3(grid), dim3(64 * WM * WN), 0,
-                           stream, p, tiles_m, (int)ntiles);
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true>), dim3(grid), dim3(64 * WM * WN), 0,
+                              stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
     else
-        hipLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false>), dim3(grid), dim3(64 * WM * WN), 0,
-                           stream, p, tiles_m, (int)ntiles);
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false>), dim3(grid), dim3(64 * WM * WN), 0,
+                              stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -270,7 +270,9 @@ int launch_inst(const StreamParams& p, int ranges, hipStream_t stream) {
     const int wpb = mblocks < 4 ? mblocks : 4;
     dim3 grid((unsigned)ranges, (unsigned)((mblocks + wpb - 1) / wpb));
     const size_t lds = (CWT > CW) ? (size_t)wpb * kPassCols * 64 * sizeof(int32_t) : 0;
-    hipLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U>), grid, dim3(64 * wpb), lds, stream, p);
+    const LaunchTiming t = take_launch_timing();
+    hipExtLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U>), grid, dim3(64 * wpb), lds, stream, t.start,
+                          t.stop, 0, p);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
