@@ -125,6 +125,28 @@ int fatnn_pack_ternary_bordered(const int8_t *levels, const int64_t dims[4], int
                                 void *packed, size_t packed_bytes, int32_t *n_invalid, void *stream);
 
 /*
+ * Algorithm 1, step 1 as written: quantize full-precision data with the learned step
+ * sizes and pack.  Weights and real-valued (FATNN_SYM) activations use the weight
+ * quantizer of Eq. 8 / Eq. 9, level = Q^w(p) + 1; non-negative (FATNN_RELU) activations
+ * use Eq. 10 (its misprinted parenthesis read as clip((p - alpha1) / alpha2, 0, 1)),
+ * level = Q^a(p).  Rounding is round-half-to-even and every operation of the formulas
+ * is a float32 operation; the kernel compares against the exact float32 break points
+ * of those formulas, so the result equals normalise-saturate-round bit for bit.
+ *   x             device float32; layout FATNN_ROWMAJOR_K, FATNN_NHWC or FATNN_OHWI
+ *                 (K contiguous), 4-byte aligned (16-byte for the bordered form)
+ *   alpha1/2      step sizes, finite and > 0 (else FATNN_ERR_SHAPE); act_mode is ignored
+ *                 for role FATNN_WEIGHT
+ *   n_invalid     NaN inputs are counted there and packed as the value 0
+ * Buffers and sizes as for fatnn_pack_ternary / fatnn_pack_ternary_bordered.
+ */
+int fatnn_quantize_pack(const float *x, int layout, const int64_t dims[4], int role, int act_mode,
+                        float alpha1, float alpha2, void *packed, size_t packed_bytes, int32_t *n_invalid,
+                        void *stream);
+int fatnn_quantize_pack_bordered(const float *x, const int64_t dims[4], int border, int act_mode,
+                                 float alpha1, float alpha2, void *packed, size_t packed_bytes,
+                                 int32_t *n_invalid, void *stream);
+
+/*
  * Ternary GEMM through Eq. 3:  C[m][n] = sum_k w[m][k] * a[n][k].
  *   Wp            packed weights  [M][Kw] (+ constants), from fatnn_pack_ternary(role WEIGHT)
  *   Ap            packed activations [N][Kw], from fatnn_pack_ternary(role ACT)

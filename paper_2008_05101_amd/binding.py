@@ -21,7 +21,8 @@ X_PLAIN, X_BORDERED = 0, 1
 EXPORTS = [
     "fatnn_words_per_row", "fatnn_packed_bytes", "fatnn_weight_consts_offset",
     "fatnn_weight_interleaved_offset", "fatnn_pack_ternary", "fatnn_bordered_act_bytes",
-    "fatnn_pack_ternary_bordered", "fatnn_pack_twobit_bordered",
+    "fatnn_pack_ternary_bordered", "fatnn_pack_twobit_bordered", "fatnn_quantize_pack",
+    "fatnn_quantize_pack_bordered",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
     "fatnn_twobit_conv2d", "fatnn_time_next_launch", "fatnn_status_str", "fatnn_version",
 ]
@@ -64,6 +65,9 @@ def lib() -> ctypes.CDLL:
         l.fatnn_bordered_act_bytes.restype = sz
         l.fatnn_pack_ternary_bordered.argtypes = [vp, dims4, i32, i32, vp, sz, vp, vp]
         l.fatnn_pack_twobit_bordered.argtypes = [vp, dims4, i32, vp, sz, vp, vp]
+        f32 = ctypes.c_float
+        l.fatnn_quantize_pack.argtypes = [vp, i32, dims4, i32, i32, f32, f32, vp, sz, vp, vp]
+        l.fatnn_quantize_pack_bordered.argtypes = [vp, dims4, i32, i32, f32, f32, vp, sz, vp, vp]
         l.fatnn_twobit_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp]
         l.fatnn_twobit_conv2d.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
         l.fatnn_time_next_launch.argtypes = [vp, vp]
@@ -205,6 +209,37 @@ def pack_twobit_bordered(codes: torch.Tensor, border: int, out: Optional[torch.T
         out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8, device=codes.device)
     _check(lib().fatnn_pack_twobit_bordered(_ptr(codes), dims, border, _ptr(out), out.numel(), _ptr(n_invalid),
                                             _stream()), "fatnn_pack_twobit_bordered")
+    return out
+
+
+def quantize_pack(x: torch.Tensor, role: int, act_mode: int, alpha1: float, alpha2: float,
+                  layout: int = ROWMAJOR_K, out: Optional[torch.Tensor] = None,
+                  n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fatnn_quantize_pack: float32 tensor -> packed plane words through the paper's quantizer."""
+    x = _dev(x, torch.float32, "x")
+    dims, shape = _dims4(layout, x)
+    rows, K = _rows_k(layout, shape)
+    nbytes = packed_bytes(role, rows, K) if K >= 1 else 0
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    _check(lib().fatnn_quantize_pack(_ptr(x), layout, dims, role, act_mode, alpha1, alpha2, _ptr(out), out.numel(),
+                                     _ptr(n_invalid), _stream()), "fatnn_quantize_pack")
+    return out
+
+
+def quantize_pack_bordered(x: torch.Tensor, border: int, act_mode: int, alpha1: float, alpha2: float,
+                           out: Optional[torch.Tensor] = None,
+                           n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+    x = _dev(x, torch.float32, "x")
+    if x.dim() != 4:
+        raise ValueError("x must be NHWC")
+    B, H, W, C = x.shape
+    dims = (ctypes.c_int64 * 4)(B, H, W, C)
+    if out is None:
+        out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8, device=x.device)
+    _check(lib().fatnn_quantize_pack_bordered(_ptr(x), dims, border, act_mode, alpha1, alpha2, _ptr(out),
+                                              out.numel(), _ptr(n_invalid), _stream()),
+           "fatnn_quantize_pack_bordered")
     return out
 
 

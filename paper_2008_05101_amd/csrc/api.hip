@@ -4,6 +4,7 @@
 #include "../../include/fatnn.h"
 #include "fatnn_device.h"
 
+#include <math.h>
 #include <stdlib.h>
 
 using namespace fatnn;
@@ -258,6 +259,54 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
     return launch_gemm(p, op, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
 }
 
+// Level that Eq. 9 (weights, real-valued activations) or Eq. 10 (ReLU activations) gives to p,
+// with every operation in float32 and round-half-to-even.
+int quantizer_level(float p, bool relu, float a1, float a2) {
+    if (!relu) {
+        const float neg = nearbyintf(fminf(fmaxf(p / a1, -1.0f), 0.0f));
+        const float pos = nearbyintf(fminf(fmaxf(p / a2, 0.0f), 1.0f));
+        return (int)(neg + pos) + 1;
+    }
+    const float first = nearbyintf(fminf(fmaxf(p / a1, 0.0f), 1.0f));
+    const float second = nearbyintf(fminf(fmaxf((p - a1) / a2, 0.0f), 1.0f));
+    return (int)(first + second);
+}
+
+// The quantizer is monotone in p, so "level >= L" holds exactly for p >= some float t.  Starts
+// at the real-number threshold and walks to the exact float32 break point.
+bool exact_threshold(int L, bool relu, float a1, float a2, float* t_out) {
+    float guess;
+    if (!relu)
+        guess = (L == 1) ? -0.5f * a1 : 0.5f * a2;
+    else
+        guess = (L == 1) ? 0.5f * a1 : a1 + 0.5f * a2;
+    float p = guess;
+    for (int it = 0; it < 4096; ++it) {
+        if (quantizer_level(p, relu, a1, a2) >= L) {
+            const float below = nextafterf(p, -INFINITY);
+            if (quantizer_level(below, relu, a1, a2) < L) {
+                *t_out = p;
+                return true;
+            }
+            p = below;
+        } else {
+            p = nextafterf(p, INFINITY);
+        }
+    }
+    return false;
+}
+
+int quant_setup(int role, int act_mode, float alpha1, float alpha2, float* t1, float* t2, uint32_t* nan_lo) {
+    if (role != FATNN_WEIGHT && role != FATNN_ACT) return FATNN_ERR_UNSUPPORTED;
+    if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
+    if (!(alpha1 > 0.0f) || !(alpha2 > 0.0f) || !isfinite(alpha1) || !isfinite(alpha2)) return FATNN_ERR_SHAPE;
+    const bool relu = role == FATNN_ACT && act_mode == FATNN_RELU;
+    if (!exact_threshold(1, relu, alpha1, alpha2, t1) || !exact_threshold(2, relu, alpha1, alpha2, t2))
+        return FATNN_ERR_UNSUPPORTED;
+    *nan_lo = relu ? 0u : 1u;
+    return FATNN_OK;
+}
+
 int pack_bordered_common(const int8_t* levels, const int64_t dims[4], int border, int kind, plane2 border_word,
                          void* packed, size_t packed_bytes, int32_t* n_invalid, void* stream) {
     if (dims == nullptr) return FATNN_ERR_NULL;
@@ -313,6 +362,64 @@ int fatnn_pack_twobit(const int8_t* codes, int layout, const int64_t dims[4], in
                       size_t packed_bytes, int32_t* n_invalid, void* stream) {
     if (role != FATNN_WEIGHT && role != FATNN_ACT) return FATNN_ERR_UNSUPPORTED;
     return pack_common(codes, layout, dims, PACK_TWOBIT, role, packed, packed_bytes, n_invalid, stream);
+}
+
+int fatnn_quantize_pack(const float* x, int layout, const int64_t dims[4], int role, int act_mode, float alpha1,
+                        float alpha2, void* packed, size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    if (dims == nullptr) return FATNN_ERR_NULL;
+    if (layout != FATNN_ROWMAJOR_K && layout != FATNN_NHWC && layout != FATNN_OHWI) return FATNN_ERR_UNSUPPORTED;
+    PackShape s;
+    int rc = pack_shape(layout, dims, &s);
+    if (rc != FATNN_OK) return rc;
+    float t1, t2;
+    uint32_t nan_lo;
+    rc = quant_setup(role, act_mode, alpha1, alpha2, &t1, &t2, &nan_lo);
+    if (rc != FATNN_OK) return rc;
+    if (s.rows == 0) return FATNN_OK;
+    if (x == nullptr || packed == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(packed, 16) || !aligned(x, 4) || !aligned(n_invalid, 4)) return FATNN_ERR_ALIGN;
+    if (packed_bytes < fatnn_packed_bytes(role, s.rows, s.K)) return FATNN_ERR_SIZE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    plane2* out = reinterpret_cast<plane2*>(packed);
+    if (launch_quantize_pack(x, s.rows, s.K, role == FATNN_WEIGHT ? PACK_WEIGHT : PACK_ACT, t1, t2, nan_lo, out,
+                             n_invalid, st) != 0)
+        return FATNN_ERR_HIP;
+    if (role == FATNN_WEIGHT) {
+        const int64_t Kw = fatnn_words_per_row(s.K);
+        char* base = reinterpret_cast<char*>(packed);
+        int32_t* consts = reinterpret_cast<int32_t*>(base + fatnn_weight_consts_offset(s.rows, s.K));
+        if (launch_row_constants(out, s.rows, Kw, consts, consts + s.rows, st) != 0) return FATNN_ERR_HIP;
+        plane2* inter = reinterpret_cast<plane2*>(base + fatnn_weight_interleaved_offset(s.rows, s.K));
+        if (launch_interleave_weights(out, s.rows, Kw, inter, st) != 0) return FATNN_ERR_HIP;
+    }
+    return FATNN_OK;
+}
+
+int fatnn_quantize_pack_bordered(const float* x, const int64_t dims[4], int border, int act_mode, float alpha1,
+                                 float alpha2, void* packed, size_t packed_bytes, int32_t* n_invalid, void* stream) {
+    if (dims == nullptr) return FATNN_ERR_NULL;
+    const int64_t B = dims[0], H = dims[1], W = dims[2], C = dims[3];
+    if (B < 0 || H < 1 || W < 1 || C < 1) return FATNN_ERR_SHAPE;
+    if (border < 0 || border > 1) return FATNN_ERR_UNSUPPORTED;
+    if (C % 32 != 0) return FATNN_ERR_UNSUPPORTED;
+    if (H > 65535 || W > 65535 || C > FATNN_MAX_K) return FATNN_ERR_SIZE;
+    if (B != 0 && (H + 2) * (W + 2) > kMaxRows / B) return FATNN_ERR_SIZE;
+    float t1, t2;
+    uint32_t nan_lo;
+    int rc = quant_setup(FATNN_ACT, act_mode, alpha1, alpha2, &t1, &t2, &nan_lo);
+    if (rc != FATNN_OK) return rc;
+    if (x == nullptr && B > 0) return FATNN_ERR_NULL;
+    if (packed == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(packed, 16) || !aligned(x, 16) || !aligned(n_invalid, 4)) return FATNN_ERR_ALIGN;
+    if (packed_bytes < fatnn_bordered_act_bytes(B, H, W, C, border)) return FATNN_ERR_SIZE;
+    plane2 bw;
+    bw.x = 0u;
+    bw.y = act_mode == FATNN_SYM ? 0xFFFFFFFFu : 0u;
+    return launch_quantize_pack_bordered(x, B, H, W, C, border, bw, FATNN_BORDER_SLACK_PIXELS, t1, t2, nan_lo,
+                                         reinterpret_cast<plane2*>(packed), n_invalid,
+                                         reinterpret_cast<hipStream_t>(stream)) == 0
+               ? FATNN_OK
+               : FATNN_ERR_HIP;
 }
 
 int fatnn_ternary_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int act_mode,

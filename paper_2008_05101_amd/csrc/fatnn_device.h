@@ -32,6 +32,12 @@ int launch_pack_contiguous(const int8_t* levels, int64_t rows, int64_t K, int ki
                            int32_t* n_invalid, hipStream_t stream);
 int launch_pack_gather(const int8_t* levels, int64_t rows, int64_t K, GatherDesc g, int kind,
                        plane2* packed, int32_t* n_invalid, hipStream_t stream);
+// Quantize-and-pack from float32: level = (p >= t1) + (p >= t2); nan_lo = low plane bit given to NaN.
+int launch_quantize_pack(const float* x, int64_t rows, int64_t K, int kind, float t1, float t2, uint32_t nan_lo,
+                         plane2* packed, int32_t* n_invalid, hipStream_t stream);
+int launch_quantize_pack_bordered(const float* x, int64_t B, int64_t H, int64_t W, int64_t C, int border,
+                                  plane2 border_word, int64_t slack_pixels, float t1, float t2, uint32_t nan_lo,
+                                  plane2* packed, int32_t* n_invalid, hipStream_t stream);
 int launch_interleave_weights(const plane2* packed, int64_t rows, int64_t Kw, plane2* inter, hipStream_t stream);
 int launch_row_constants(const plane2* packed, int64_t rows, int64_t Kw, int32_t* nnz, int32_t* npos,
                          hipStream_t stream);

@@ -212,6 +212,104 @@ __global__ __launch_bounds__(256) void pack_bordered_kernel(const int8_t* __rest
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Algorithm 1, step 1 as the paper writes it: full-precision values are compared with the
+// quantisation thresholds and assigned their codec.  The thresholds are the exact
+// float32 break points of Eq. 9 / Eq. 10 (found on the host), so two comparisons per
+// element reproduce normalise-saturate-round bit for bit.
+//   level = (p >= t1) + (p >= t2);  NaN counts as invalid and is packed as the value 0.
+struct QuantThresholds {
+    float t1, t2;
+    uint32_t nan_lo;   // low plane bit of the value 0: 1 (level 1) for weights / symmetric, 0 in ReLU mode
+};
+
+__device__ __forceinline__ void quant_bits(float v, int e, const QuantThresholds& q, uint32_t& p1, uint32_t& p0,
+                                           uint32_t& bad) {
+    const uint32_t ge1 = v >= q.t1 ? 1u : 0u;
+    const uint32_t ge2 = v >= q.t2 ? 1u : 0u;
+    const uint32_t nan = (v != v) ? 1u : 0u;
+    p1 |= ge2 << e;
+    p0 |= (ge1 | (nan & q.nan_lo)) << e;
+    bad |= nan << e;
+}
+
+template <int KIND>
+__device__ __forceinline__ plane2 quant_word(const float* __restrict__ src, int64_t valid, bool vec,
+                                             const QuantThresholds& q, uint32_t& bad) {
+    // `valid` = number of real elements among the 32 of this word (tail slots are the value 0: level 1)
+    uint32_t p1 = 0, p0 = 0;
+    bad = 0;
+    if (vec) {
+        const float4* s4 = reinterpret_cast<const float4*>(src);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            if (g * 4 < valid) {
+                const float4 v = s4[g];
+                quant_bits(v.x, g * 4 + 0, q, p1, p0, bad);
+                quant_bits(v.y, g * 4 + 1, q, p1, p0, bad);
+                quant_bits(v.z, g * 4 + 2, q, p1, p0, bad);
+                quant_bits(v.w, g * 4 + 3, q, p1, p0, bad);
+            } else {
+                p0 |= 0xFu << (g * 4);
+            }
+        }
+    } else {
+#pragma unroll 8
+        for (int e = 0; e < 32; ++e) {
+            if (e < valid)
+                quant_bits(src[e], e, q, p1, p0, bad);
+            else
+                p0 |= 1u << e;
+        }
+    }
+    return finish_word<KIND>(p1, p0);
+}
+
+template <int KIND>
+__global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restrict__ x, int64_t rows, int64_t K,
+                                                            int64_t Kw, bool vec, QuantThresholds q,
+                                                            plane2* __restrict__ packed,
+                                                            int32_t* __restrict__ n_invalid) {
+    const int64_t total = rows * Kw;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += stride) {
+        const int64_t row = id / Kw;
+        const int64_t kw = id - row * Kw;
+        const int64_t left = K - kw * 32;
+        uint32_t bad;
+        packed[id] = quant_word<KIND>(x + row * K + kw * 32, left < 32 ? left : 32, vec, q, bad);
+        if (bad != 0 && n_invalid != nullptr) atomicAdd(n_invalid, __popc(bad));
+    }
+}
+
+__global__ __launch_bounds__(256) void quantize_pack_bordered_kernel(const float* __restrict__ x, int64_t B, int64_t H,
+                                                                     int64_t W, int64_t Cw, int border,
+                                                                     plane2 border_word, int64_t total,
+                                                                     QuantThresholds q, plane2* __restrict__ packed,
+                                                                     int32_t* __restrict__ n_invalid) {
+    const int64_t Hp = H + 2 * border, Wp = W + 2 * border;
+    const int64_t npix = B * Hp * Wp;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += stride) {
+        const int64_t pix = id / Cw;
+        const int64_t cw = id - pix * Cw;
+        plane2 out = border_word;
+        if (pix < npix) {
+            const int64_t wp = pix % Wp;
+            const int64_t t = pix / Wp;
+            const int64_t hp = t % Hp;
+            const int64_t b = t / Hp;
+            const int64_t h = hp - border, w = wp - border;
+            if (h >= 0 && h < H && w >= 0 && w < W) {
+                uint32_t bad;
+                out = quant_word<PACK_ACT>(x + (((b * H + h) * W + w) * Cw + cw) * 32, 32, true, q, bad);
+                if (bad != 0 && n_invalid != nullptr) atomicAdd(n_invalid, __popc(bad));
+            }
+        }
+        packed[id] = out;
+    }
+}
+
 // Second copy of the weight words with the 64 rows of a block contiguous per k-word.
 __global__ __launch_bounds__(256) void interleave_weights_kernel(const plane2* __restrict__ packed, int64_t rows,
                                                                  int64_t Kw, int64_t total,
@@ -304,6 +402,35 @@ int launch_pack_bordered(const int8_t* levels, int64_t B, int64_t H, int64_t W, 
                            border_word, total, packed, n_invalid);
     else
         return -1;
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_quantize_pack(const float* x, int64_t rows, int64_t K, int kind, float t1, float t2, uint32_t nan_lo,
+                         plane2* packed, int32_t* n_invalid, hipStream_t stream) {
+    const int64_t Kw = (K + 31) / 32;
+    const int64_t total = rows * Kw;
+    if (total == 0) return 0;
+    const bool vec = (K % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15u) == 0);
+    QuantThresholds q{t1, t2, nan_lo};
+    dim3 grid(grid_for(total, 256)), block(256);
+    if (kind == PACK_WEIGHT)
+        hipLaunchKernelGGL((quantize_pack_kernel<PACK_WEIGHT>), grid, block, 0, stream, x, rows, K, Kw, vec, q, packed,
+                           n_invalid);
+    else
+        hipLaunchKernelGGL((quantize_pack_kernel<PACK_ACT>), grid, block, 0, stream, x, rows, K, Kw, vec, q, packed,
+                           n_invalid);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_quantize_pack_bordered(const float* x, int64_t B, int64_t H, int64_t W, int64_t C, int border,
+                                  plane2 border_word, int64_t slack_pixels, float t1, float t2, uint32_t nan_lo,
+                                  plane2* packed, int32_t* n_invalid, hipStream_t stream) {
+    const int64_t Cw = C / 32;
+    const int64_t total = (B * (H + 2 * border) * (W + 2 * border) + slack_pixels) * Cw;
+    if (total == 0) return 0;
+    QuantThresholds q{t1, t2, nan_lo};
+    hipLaunchKernelGGL(quantize_pack_bordered_kernel, dim3(grid_for(total, 256)), dim3(256), 0, stream, x, B, H, W, Cw,
+                       border, border_word, total, q, packed, n_invalid);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

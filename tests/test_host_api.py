@@ -32,7 +32,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert len(names) >= 14
+    assert len(names) >= 18
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in fatnn.h but not exported"
     assert sorted(binding.EXPORTS) == names
@@ -118,6 +118,28 @@ def test_bordered_pack_argument_errors(lib):
     assert f(FAKE, dims(2, 4, 4, 64), 1, 0, FAKE, 100, None, None) == E_SIZE
     g = lib.fatnn_pack_twobit_bordered
     assert g(FAKE, dims(2, 4, 4, 64), 1, FAKE, 100, None, None) == E_SIZE
+
+
+def test_quantize_pack_argument_errors(lib):
+    f = lib.fatnn_quantize_pack
+    f.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.c_int, ctypes.c_int,
+                  ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    big = 1 << 30
+    assert f(FAKE, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 0, 0.0, 1.0, FAKE, big, None, None) == E_SHAPE
+    assert f(FAKE, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 0, 1.0, -2.0, FAKE, big, None, None) == E_SHAPE
+    assert f(FAKE, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 0, float("nan"), 1.0, FAKE, big, None, None) == E_SHAPE
+    assert f(FAKE, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 0, float("inf"), 1.0, FAKE, big, None, None) == E_SHAPE
+    assert f(FAKE, fatnn.OIHW, dims(4, 32, 3, 3), fatnn.WEIGHT, 0, 1.0, 1.0, FAKE, big, None, None) == E_UNSUP
+    assert f(FAKE, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), 9, 0, 1.0, 1.0, FAKE, big, None, None) == E_UNSUP
+    assert f(FAKE, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 5, 1.0, 1.0, FAKE, big, None, None) == E_UNSUP
+    assert f(None, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 0, 1.0, 1.0, FAKE, big, None, None) == E_NULL
+    assert f(FAKE + 2, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 0, 1.0, 1.0, FAKE, big, None, None) == E_ALIGN
+    assert f(FAKE, fatnn.ROWMAJOR_K, dims(4, 8, 1, 1), fatnn.ACT, 0, 1.0, 1.0, FAKE, 8, None, None) == E_SIZE
+    assert f(None, fatnn.ROWMAJOR_K, dims(0, 8, 1, 1), fatnn.ACT, 0, 1.0, 1.0, None, 0, None, None) == OK
+    g = lib.fatnn_quantize_pack_bordered
+    assert g(FAKE, dims(2, 4, 4, 64), 1, 0, 1.0, 0.0, FAKE, big, None, None) == E_SHAPE
+    assert g(FAKE, dims(2, 4, 4, 48), 1, 0, 1.0, 1.0, FAKE, big, None, None) == E_UNSUP
+    assert g(FAKE, dims(2, 4, 4, 64), 1, 0, 1.0, 1.0, FAKE, 100, None, None) == E_SIZE
 
 
 def test_gemm_argument_errors(lib):
