@@ -177,6 +177,29 @@ int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B
                          const float *scale, const float *bias, float *Yf, void *stream);
 
 /*
+ * Layer chaining (Supplementary S1: batch norm folded into the layer, ReLU and the skip
+ * connection fused with the packing of the next layer's input).  Same convolution as
+ * fatnn_ternary_conv2d on a BORDERED input, but instead of the int32 result it produces
+ *     f = scale[m] * C (+ bias[m]) (+ skip[n][m]),  f = max(f, 0) if relu != 0      (fp32, one
+ *                                                   rounding per operation)
+ *     level = quantizer of the NEXT layer applied to f: Eq. 9 for out_act_mode FATNN_SYM,
+ *             Eq. 10 for FATNN_RELU, with step sizes alpha1, alpha2 (as fatnn_quantize_pack)
+ * and writes the levels, packed, into the interior of the next layer's bordered input
+ *     Xnext = [B][Ho + 2*out_border][Wo + 2*out_border][Cout/32] (+ slack),
+ * whose ring must have been initialised once with fatnn_bordered_act_init (the ring is
+ * never written here).  Yf (optional, NHWC fp32) receives f, e.g. as the next block's skip
+ * input.  skip (optional) is NHWC fp32 [B][Ho][Wo][Cout].  Cout must be a multiple of 32.
+ * Shapes the streaming kernel does not cover return FATNN_ERR_UNSUPPORTED.
+ */
+int fatnn_bordered_act_init(void *packed, size_t packed_bytes, int64_t B, int64_t H, int64_t W, int64_t C,
+                            int border, int act_mode, void *stream);
+int fatnn_ternary_conv2d_chain(const void *Wp, const void *Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                               int64_t Cout, int R, int S, int stride, int pad, int act_mode,
+                               const float *scale, const float *bias, const float *skip, int relu,
+                               float alpha1, float alpha2, int out_act_mode, int out_border, void *Xnext,
+                               size_t xnext_bytes, float *Yf, void *stream);
+
+/*
  * Conventional two-bit path (Eq. 2 with two bit-planes per operand and the binary
  * inner product of Eq. 1): four logic operations and four popcounts per packed
  * word pair where Eq. 3 needs two and two.  It exists so the paper's O(4N) ->

@@ -22,7 +22,7 @@ EXPORTS = [
     "fatnn_words_per_row", "fatnn_packed_bytes", "fatnn_weight_consts_offset",
     "fatnn_weight_interleaved_offset", "fatnn_pack_ternary", "fatnn_bordered_act_bytes",
     "fatnn_pack_ternary_bordered", "fatnn_pack_twobit_bordered", "fatnn_quantize_pack",
-    "fatnn_quantize_pack_bordered",
+    "fatnn_quantize_pack_bordered", "fatnn_bordered_act_init", "fatnn_ternary_conv2d_chain",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
     "fatnn_twobit_conv2d", "fatnn_time_next_launch", "fatnn_status_str", "fatnn_version",
 ]
@@ -68,6 +68,9 @@ def lib() -> ctypes.CDLL:
         f32 = ctypes.c_float
         l.fatnn_quantize_pack.argtypes = [vp, i32, dims4, i32, i32, f32, f32, vp, sz, vp, vp]
         l.fatnn_quantize_pack_bordered.argtypes = [vp, dims4, i32, i32, f32, f32, vp, sz, vp, vp]
+        l.fatnn_bordered_act_init.argtypes = [vp, sz, i64, i64, i64, i64, i32, i32, vp]
+        l.fatnn_ternary_conv2d_chain.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp,
+                                                 i32, f32, f32, i32, i32, vp, sz, vp, vp]
         l.fatnn_twobit_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp]
         l.fatnn_twobit_conv2d.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
         l.fatnn_time_next_launch.argtypes = [vp, vp]
@@ -278,6 +281,30 @@ def ternary_conv2d(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H: int,
                                       _ptr(out), _ptr(scale), _ptr(bias), _ptr(out_f), _stream()),
            "fatnn_ternary_conv2d")
     return out, out_f
+
+
+def bordered_act_init(B: int, H: int, W: int, C: int, border: int, act_mode: int,
+                      out: Optional[torch.Tensor] = None, device=None) -> torch.Tensor:
+    """Allocates (or takes) a bordered activation buffer and fills it with the value 0."""
+    if out is None:
+        out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8,
+                          device=device if device is not None else "cuda")
+    _check(lib().fatnn_bordered_act_init(_ptr(out), out.numel(), B, H, W, C, border, act_mode, _stream()),
+           "fatnn_bordered_act_init")
+    return out
+
+
+def ternary_conv2d_chain(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H: int, W: int, Cout: int,
+                         R: int, S: int, stride: int, pad: int, act_mode: int, scale: torch.Tensor,
+                         bias: Optional[torch.Tensor], skip: Optional[torch.Tensor], relu: bool,
+                         alpha1: float, alpha2: float, out_act_mode: int, out_border: int, x_next: torch.Tensor,
+                         out_f: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fatnn_ternary_conv2d_chain: conv + affine (+skip, ReLU) + next layer's quantizer + packing."""
+    _check(lib().fatnn_ternary_conv2d_chain(_ptr(Wp), _ptr(Xp), B, Cin, H, W, Cout, R, S, stride, pad, act_mode,
+                                            _ptr(scale), _ptr(bias), _ptr(skip), 1 if relu else 0, alpha1, alpha2,
+                                            out_act_mode, out_border, _ptr(x_next), x_next.numel(), _ptr(out_f),
+                                            _stream()), "fatnn_ternary_conv2d_chain")
+    return x_next
 
 
 def twobit_gemm(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, basis: int = BASIS_TERNARY,

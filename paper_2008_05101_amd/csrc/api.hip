@@ -205,9 +205,18 @@ int stream_ranges(int64_t M, int64_t ngroups, int64_t group_size, int64_t Kw, in
     return (int)ranges;
 }
 
+struct ChainArgs {
+    const float* skip;
+    int relu;
+    float t1, t2;
+    uint32_t nan_lo;
+    int out_border;
+    void* Xnext;
+};
+
 int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Cin, int64_t H, int64_t W,
              int64_t Cout, int R, int S, int stride, int pad, const ConvShape& cs, int op, int act_mode, int32_t* Y,
-             const float* scale, const float* bias, float* Yf, void* stream) {
+             const float* scale, const float* bias, float* Yf, void* stream, const ChainArgs* chain = nullptr) {
     const int Cw = (int)(Cin / 32);
     const uint32_t pad_y = (op == OP_TERNARY && act_mode == FATNN_RELU) ? 0u : 0xFFFFFFFFu;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -233,11 +242,22 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
         q.C = Y; q.Cf = Yf; q.ldc_n = Cout;
         q.scale = scale; q.bias = bias;
         q.B = (int32_t)B; q.Hp = (int32_t)Hs; q.Wp = (int32_t)Ws; q.Ho = (int32_t)cs.Ho; q.Wo = (int32_t)cs.Wo;
+        if (chain != nullptr) {
+            q.Xn = reinterpret_cast<plane2*>(chain->Xnext);
+            q.nborder = chain->out_border;
+            q.nHp = (int32_t)(cs.Ho + 2 * chain->out_border);
+            q.nWp = (int32_t)(cs.Wo + 2 * chain->out_border);
+            q.nCw = (int32_t)(Cout / 32);
+            q.skip = chain->skip;
+            q.t1 = chain->t1; q.t2 = chain->t2; q.nan_lo = chain->nan_lo;
+            q.relu = chain->relu;
+        }
         const int U = stream_group_size(R, Cw, stride);
         const int64_t ngroups = B * cs.Ho * ((cs.Wo + U - 1) / U);
         const int ranges = stream_ranges(Cout, ngroups, U, q.Kw, stream_max_groups_per_range(R, Cw, stride));
         return launch_stream_conv(q, op, R, Cw, stride, ranges, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
     }
+    if (chain != nullptr) return FATNN_ERR_UNSUPPORTED;   // the chaining epilogue lives in the streaming kernel
     GemmParams p{};
     p.W = reinterpret_cast<const plane2*>(Wp);
     p.A = reinterpret_cast<const plane2*>(Xp);
@@ -492,6 +512,52 @@ int fatnn_ternary_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B
         return FATNN_ERR_ALIGN;
     return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TERNARY, act_mode, Y, scale,
                     bias, Yf, stream);
+}
+
+int fatnn_bordered_act_init(void* packed, size_t packed_bytes, int64_t B, int64_t H, int64_t W, int64_t C, int border,
+                            int act_mode, void* stream) {
+    if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
+    const size_t need = fatnn_bordered_act_bytes(B, H, W, C, border);
+    if (need == 0) return (border < 0 || border > 1 || (C > 0 && C % 32 != 0)) ? FATNN_ERR_UNSUPPORTED : FATNN_ERR_SHAPE;
+    if (packed == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(packed, 16)) return FATNN_ERR_ALIGN;
+    if (packed_bytes < need) return FATNN_ERR_SIZE;
+    plane2 bw;
+    bw.x = 0u;
+    bw.y = act_mode == FATNN_SYM ? 0xFFFFFFFFu : 0u;
+    return launch_fill_words(reinterpret_cast<plane2*>(packed), (int64_t)(need / sizeof(plane2)), bw,
+                             reinterpret_cast<hipStream_t>(stream)) == 0
+               ? FATNN_OK
+               : FATNN_ERR_HIP;
+}
+
+int fatnn_ternary_conv2d_chain(const void* Wp, const void* Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
+                               int64_t Cout, int R, int S, int stride, int pad, int act_mode, const float* scale,
+                               const float* bias, const float* skip, int relu, float alpha1, float alpha2,
+                               int out_act_mode, int out_border, void* Xnext, size_t xnext_bytes, float* Yf,
+                               void* stream) {
+    ConvShape cs;
+    int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
+    if (rc != FATNN_OK) return rc;
+    if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
+    if (out_border < 0 || out_border > 1) return FATNN_ERR_UNSUPPORTED;
+    if (Cout % 32 != 0) return FATNN_ERR_UNSUPPORTED;
+    if (!stream_supported(OP_TERNARY, R, S, (int)(Cin / 32), stride)) return FATNN_ERR_UNSUPPORTED;
+    ChainArgs ch{};
+    rc = quant_setup(FATNN_ACT, out_act_mode, alpha1, alpha2, &ch.t1, &ch.t2, &ch.nan_lo);
+    if (rc != FATNN_OK) return rc;
+    if (B == 0 || Cout == 0) return FATNN_OK;
+    if (Wp == nullptr || Xp == nullptr || scale == nullptr || Xnext == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(Wp, 16) || !aligned(Xp, 16) || !aligned(Xnext, 16) || !aligned(Yf, 4) || !aligned(scale, 4) ||
+        !aligned(bias, 4) || !aligned(skip, 4))
+        return FATNN_ERR_ALIGN;
+    if (xnext_bytes < fatnn_bordered_act_bytes(B, cs.Ho, cs.Wo, Cout, out_border)) return FATNN_ERR_SIZE;
+    ch.skip = skip;
+    ch.relu = relu != 0;
+    ch.out_border = out_border;
+    ch.Xnext = Xnext;
+    return run_conv(Wp, Xp, FATNN_X_BORDERED, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TERNARY, act_mode, nullptr,
+                    scale, bias, Yf, stream, &ch);
 }
 
 int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int basis, int32_t* C,

@@ -38,6 +38,7 @@ int launch_quantize_pack(const float* x, int64_t rows, int64_t K, int kind, floa
 int launch_quantize_pack_bordered(const float* x, int64_t B, int64_t H, int64_t W, int64_t C, int border,
                                   plane2 border_word, int64_t slack_pixels, float t1, float t2, uint32_t nan_lo,
                                   plane2* packed, int32_t* n_invalid, hipStream_t stream);
+int launch_fill_words(plane2* dst, int64_t count, plane2 word, hipStream_t stream);
 int launch_interleave_weights(const plane2* packed, int64_t rows, int64_t Kw, plane2* inter, hipStream_t stream);
 int launch_row_constants(const plane2* packed, int64_t rows, int64_t Kw, int32_t* nnz, int32_t* npos,
                          hipStream_t stream);
@@ -92,6 +93,14 @@ struct StreamParams {
     const float* scale;
     const float* bias;
     int32_t B, Hp, Wp, Ho, Wo;
+    // Layer-chaining epilogue (Xn != nullptr): affine, optional skip and ReLU in fp32, then the
+    // next layer's activation quantizer and packing straight into its bordered input buffer.
+    plane2* Xn;             // [B][nHp][nWp][nCw] word pairs, ring already initialised
+    int32_t nHp, nWp, nCw, nborder;
+    const float* skip;      // fp32 NHWC [B][Ho][Wo][M] or null
+    float t1, t2;           // level = (f >= t1) + (f >= t2)
+    uint32_t nan_lo;
+    int32_t relu;
 };
 
 bool stream_supported(int op, int R, int S, int Cw, int stride);

@@ -310,6 +310,11 @@ __global__ __launch_bounds__(256) void quantize_pack_bordered_kernel(const float
     }
 }
 
+__global__ __launch_bounds__(256) void fill_words_kernel(plane2* __restrict__ dst, int64_t count, plane2 word) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < count; id += stride) dst[id] = word;
+}
+
 // Second copy of the weight words with the 64 rows of a block contiguous per k-word.
 __global__ __launch_bounds__(256) void interleave_weights_kernel(const plane2* __restrict__ packed, int64_t rows,
                                                                  int64_t Kw, int64_t total,
@@ -431,6 +436,12 @@ int launch_quantize_pack_bordered(const float* x, int64_t B, int64_t H, int64_t 
     QuantThresholds q{t1, t2, nan_lo};
     hipLaunchKernelGGL(quantize_pack_bordered_kernel, dim3(grid_for(total, 256)), dim3(256), 0, stream, x, B, H, W, Cw,
                        border, border_word, total, q, packed, n_invalid);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_fill_words(plane2* dst, int64_t count, plane2 word, hipStream_t stream) {
+    if (count == 0) return 0;
+    hipLaunchKernelGGL(fill_words_kernel, dim3(grid_for(count, 256)), dim3(256), 0, stream, dst, count, word);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     float sc = 0.f, bs = 0.f;
     if (m_ok) {
         if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
-        if (p.Cf != nullptr) {
+        if (p.Cf != nullptr || p.Xn != nullptr) {
             sc = p.scale[m];
             if (p.bias != nullptr) bs = p.bias[m];
         }
@@ -186,6 +186,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         constexpr int PAR = decltype(par_tag)::value;
         const int wo0 = wg * U;
         const int64_t n0 = ((int64_t)b * p.Ho + ho) * p.Wo + wo0;
+        // first pixel of the group in the next layer's bordered input (chaining epilogue only)
+        const int64_t nx0 = ((int64_t)b * p.nHp + ho + p.nborder) * p.nWp + wo0 + p.nborder;
         uint32_t goff_next = goff;
         if (g + 1 < g_end) {
             advance();
@@ -215,6 +217,33 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         if (NPASS > 1 && pass + 1 < NPASS) {
 #pragma unroll
             for (int u = 0; u < U; ++u) my_partials[(col_local + u) * 64] = acc[u];
+            return;
+        }
+        if (p.Xn != nullptr) {
+            // Layer chaining (Supplementary S1: batch norm folded into the layer, ReLU and the skip
+            // connection fused, packing fused): the 64 channels of a wavefront are 64 lanes, so a
+            // wave-wide ballot of the two quantizer comparisons IS the pair of plane words.
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (wo0 + u >= p.Wo) break;
+                const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : p.K - (acc[u] >> 1);
+                float f = sc * (float)v;
+                if (p.bias != nullptr) f = f + bs;
+                const int64_t o = (n0 + u) * p.ldc_n + m;
+                if (p.skip != nullptr && m_ok) f = f + p.skip[o];
+                if (p.relu) f = fmaxf(f, 0.0f);
+                if (p.Cf != nullptr && m_ok) __builtin_nontemporal_store(f, &p.Cf[o]);
+                const bool nan = f != f;
+                const uint64_t lo = __ballot(m_ok && ((f >= p.t1) || (nan && p.nan_lo != 0u)));
+                const uint64_t hi = __ballot(m_ok && (f >= p.t2));
+                const int cw = 2 * mb + lane;            // lanes 0 and 1 write one word pair each
+                if (lane < 2 && cw < p.nCw) {
+                    plane2 word;
+                    word.x = (uint32_t)(lane == 0 ? hi : hi >> 32);
+                    word.y = (uint32_t)(lane == 0 ? lo : lo >> 32);
+                    p.Xn[(nx0 + u) * p.nCw + cw] = word;
+                }
+            }
             return;
         }
 #pragma unroll

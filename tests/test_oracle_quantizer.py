@@ -87,3 +87,20 @@ def test_infinities_saturate():
     p = np.array([-np.inf, np.inf], np.float32)
     assert q.quantize_weight(p, 0.3, 0.4).tolist() == [-1, 1]
     assert q.quantize_relu_act(p, 0.3, 0.4).tolist() == [0, 2]
+
+
+def test_chain_epilogue_hand_example():
+    # one pixel, four channels, numbers chosen so every float32 step is exact
+    from oracle import chain
+    C = np.array([[[[4, -2, 10, 1]]]], np.int32)
+    scale = np.array([0.5, 0.25, 0.125, 2.0], np.float32)
+    bias = np.array([-1.0, 0.0, 0.5, 0.25], np.float32)
+    skip = np.array([[[[0.0, 1.0, -3.0, 0.0]]]], np.float32)
+    f, lv = chain.chain_epilogue(C, scale, bias, skip, True, 1, 1.0, 1.0)
+    #  f = 0.5*4-1+0 = 1 ; 0.25*-2+0+1 = 0.5 ; 0.125*10+0.5-3 = -1.25 -> relu 0 ; 2*1+0.25 = 2.25
+    assert f.reshape(-1).tolist() == [1.0, 0.5, 0.0, 2.25]
+    # Eq. 10 with alpha1 = alpha2 = 1: thresholds 0.5 (tie -> 0) and 1.5
+    assert lv.reshape(-1).tolist() == [1, 0, 0, 2]
+    f2, lv2 = chain.chain_epilogue(C, scale, bias, None, False, 0, 1.0, 1.0)
+    assert f2.reshape(-1).tolist() == [1.0, -0.5, 1.75, 2.25]
+    assert lv2.reshape(-1).tolist() == [2, 1, 2, 2]      # Eq. 9: -0.5 is a tie -> 0 -> level 1
