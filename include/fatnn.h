@@ -66,7 +66,7 @@ enum {                                                    /* layout of a level t
     FATNN_OIHW = 3,       /* dims = {O, C, R, S}: same packed result as OHWI (gathering, slow path)   */
     FATNN_NCHW = 4        /* dims = {B, C, H, W}: same packed result as NHWC (gathering, slow path)   */
 };
-enum { FATNN_X_PLAIN = 0, FATNN_X_BORDERED = 1 };         /* layout of packed conv activations        */
+enum { FATNN_X_PLAIN = 0, FATNN_X_BORDERED = 1, FATNN_X_BORDERED1 = 2 };  /* packed conv activations */
 enum { FATNN_BASIS_TERNARY = 0, FATNN_BASIS_UNIFORM = 1 };/* two-bit basis, see fatnn_twobit_gemm     */
 
 /* Largest supported extents: rows, columns < 2^31; K <= 2^24 (keeps |C| <= 2K exact in fp32 too). */
@@ -166,7 +166,9 @@ int fatnn_ternary_gemm(const void *Wp, const void *Ap, int64_t M, int64_t N, int
  *   Wp            packed weights from layout OHWI/OIHW: [Cout][R*S*Cin/32] (+ constants)
  *   Xp, x_layout  packed activations: FATNN_X_PLAIN = [B][H][W][Cin/32] from
  *                 fatnn_pack_ternary (NHWC/NCHW); FATNN_X_BORDERED = the bordered layout of
- *                 fatnn_pack_ternary_bordered with border == pad and the same act_mode
+ *                 fatnn_pack_ternary_bordered with border == pad and the same act_mode;
+ *                 FATNN_X_BORDERED1 = that layout with border 1 whatever pad is (a 1x1,
+ *                 pad 0 convolution reading the buffer a 3x3, pad 1 convolution also reads)
  *   Y, Yf         int32 / fp32 NHWC outputs [B][Ho][Wo][Cout], Ho = (H + 2*pad - R)/stride + 1
  *   Padding is the VALUE 0 in either act_mode.
  * Supported: R = S in {1, 3}, stride in {1, 2}, pad in {0, 1} with pad <= R/2,
@@ -179,7 +181,7 @@ int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B
 /*
  * Layer chaining (Supplementary S1: batch norm folded into the layer, ReLU and the skip
  * connection fused with the packing of the next layer's input).  Same convolution as
- * fatnn_ternary_conv2d on a BORDERED input, but instead of the int32 result it produces
+ * fatnn_ternary_conv2d on a bordered input (x_layout FATNN_X_BORDERED or _BORDERED1), but instead of the int32 result it produces
  *     f = scale[m] * C (+ bias[m]) (+ skip[n][m]),  f = max(f, 0) if relu != 0      (fp32, one
  *                                                   rounding per operation)
  *     level = quantizer of the NEXT layer applied to f: Eq. 9 for out_act_mode FATNN_SYM,
@@ -193,8 +195,8 @@ int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B
  */
 int fatnn_bordered_act_init(void *packed, size_t packed_bytes, int64_t B, int64_t H, int64_t W, int64_t C,
                             int border, int act_mode, void *stream);
-int fatnn_ternary_conv2d_chain(const void *Wp, const void *Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
-                               int64_t Cout, int R, int S, int stride, int pad, int act_mode,
+int fatnn_ternary_conv2d_chain(const void *Wp, const void *Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
+                               int64_t W, int64_t Cout, int R, int S, int stride, int pad, int act_mode,
                                const float *scale, const float *bias, const float *skip, int relu,
                                float alpha1, float alpha2, int out_act_mode, int out_border, void *Xnext,
                                size_t xnext_bytes, float *Yf, void *stream);

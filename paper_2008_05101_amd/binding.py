@@ -16,7 +16,7 @@ WEIGHT, ACT = 0, 1
 SYM, RELU = 0, 1
 ROWMAJOR_K, NHWC, OHWI, OIHW, NCHW = 0, 1, 2, 3, 4
 BASIS_TERNARY, BASIS_UNIFORM = 0, 1
-X_PLAIN, X_BORDERED = 0, 1
+X_PLAIN, X_BORDERED, X_BORDERED1 = 0, 1, 2
 
 EXPORTS = [
     "fatnn_words_per_row", "fatnn_packed_bytes", "fatnn_weight_consts_offset",
@@ -69,8 +69,8 @@ def lib() -> ctypes.CDLL:
         l.fatnn_quantize_pack.argtypes = [vp, i32, dims4, i32, i32, f32, f32, vp, sz, vp, vp]
         l.fatnn_quantize_pack_bordered.argtypes = [vp, dims4, i32, i32, f32, f32, vp, sz, vp, vp]
         l.fatnn_bordered_act_init.argtypes = [vp, sz, i64, i64, i64, i64, i32, i32, vp]
-        l.fatnn_ternary_conv2d_chain.argtypes = [vp, vp, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp,
-                                                 i32, f32, f32, i32, i32, vp, sz, vp, vp]
+        l.fatnn_ternary_conv2d_chain.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp,
+                                                 vp, i32, f32, f32, i32, i32, vp, sz, vp, vp]
         l.fatnn_twobit_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp]
         l.fatnn_twobit_conv2d.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
         l.fatnn_time_next_launch.argtypes = [vp, vp]
@@ -298,9 +298,9 @@ def ternary_conv2d_chain(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H
                          R: int, S: int, stride: int, pad: int, act_mode: int, scale: torch.Tensor,
                          bias: Optional[torch.Tensor], skip: Optional[torch.Tensor], relu: bool,
                          alpha1: float, alpha2: float, out_act_mode: int, out_border: int, x_next: torch.Tensor,
-                         out_f: Optional[torch.Tensor] = None) -> torch.Tensor:
+                         out_f: Optional[torch.Tensor] = None, x_layout: int = X_BORDERED) -> torch.Tensor:
     """fatnn_ternary_conv2d_chain: conv + affine (+skip, ReLU) + next layer's quantizer + packing."""
-    _check(lib().fatnn_ternary_conv2d_chain(_ptr(Wp), _ptr(Xp), B, Cin, H, W, Cout, R, S, stride, pad, act_mode,
+    _check(lib().fatnn_ternary_conv2d_chain(_ptr(Wp), _ptr(Xp), x_layout, B, Cin, H, W, Cout, R, S, stride, pad, act_mode,
                                             _ptr(scale), _ptr(bias), _ptr(skip), 1 if relu else 0, alpha1, alpha2,
                                             out_act_mode, out_border, _ptr(x_next), x_next.numel(), _ptr(out_f),
                                             _stream()), "fatnn_ternary_conv2d_chain")

@@ -220,10 +220,12 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
     const int Cw = (int)(Cin / 32);
     const uint32_t pad_y = (op == OP_TERNARY && act_mode == FATNN_RELU) ? 0u : 0xFFFFFFFFu;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const bool bordered = x_layout == FATNN_X_BORDERED;
-    // in the bordered layout the padding is physical: a larger image convolved without padding
-    const int64_t Hs = bordered ? H + 2 * pad : H, Ws = bordered ? W + 2 * pad : W;
-    const int pad_s = bordered ? 0 : pad;
+    const bool bordered = x_layout != FATNN_X_PLAIN;
+    // in the bordered layouts the padding is physical: a larger image convolved without padding
+    // (and, when the ring is wider than the padding, with the taps shifted inwards)
+    const int xb = x_layout == FATNN_X_BORDERED1 ? 1 : (bordered ? pad : 0);
+    const int64_t Hs = H + 2 * xb, Ws = W + 2 * xb;
+    const int pad_s = pad - xb;
     const int64_t stored_bytes = (B * Hs * Ws + FATNN_BORDER_SLACK_PIXELS) * Cw * (int64_t)sizeof(plane2);
     if (bordered && stored_bytes < 0xFFFFFFFFLL && want_stream(op, R, S, Cw, stride)) {
         StreamParams q{};
@@ -242,6 +244,7 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
         q.C = Y; q.Cf = Yf; q.ldc_n = Cout;
         q.scale = scale; q.bias = bias;
         q.B = (int32_t)B; q.Hp = (int32_t)Hs; q.Wp = (int32_t)Ws; q.Ho = (int32_t)cs.Ho; q.Wo = (int32_t)cs.Wo;
+        q.xoff = xb - pad;
         if (chain != nullptr) {
             q.Xn = reinterpret_cast<plane2*>(chain->Xnext);
             q.nborder = chain->out_border;
@@ -498,7 +501,8 @@ int fatnn_pack_twobit_bordered(const int8_t* codes, const int64_t dims[4], int b
 int fatnn_ternary_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
                          int64_t W, int64_t Cout, int R, int S, int stride, int pad, int act_mode, int32_t* Y,
                          const float* scale, const float* bias, float* Yf, void* stream) {
-    if (x_layout != FATNN_X_PLAIN && x_layout != FATNN_X_BORDERED) return FATNN_ERR_UNSUPPORTED;
+    if (x_layout != FATNN_X_PLAIN && x_layout != FATNN_X_BORDERED && x_layout != FATNN_X_BORDERED1)
+        return FATNN_ERR_UNSUPPORTED;
     ConvShape cs;
     int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
     if (rc != FATNN_OK) return rc;
@@ -531,11 +535,12 @@ int fatnn_bordered_act_init(void* packed, size_t packed_bytes, int64_t B, int64_
                : FATNN_ERR_HIP;
 }
 
-int fatnn_ternary_conv2d_chain(const void* Wp, const void* Xp, int64_t B, int64_t Cin, int64_t H, int64_t W,
-                               int64_t Cout, int R, int S, int stride, int pad, int act_mode, const float* scale,
+int fatnn_ternary_conv2d_chain(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
+                               int64_t W, int64_t Cout, int R, int S, int stride, int pad, int act_mode, const float* scale,
                                const float* bias, const float* skip, int relu, float alpha1, float alpha2,
                                int out_act_mode, int out_border, void* Xnext, size_t xnext_bytes, float* Yf,
                                void* stream) {
+    if (x_layout != FATNN_X_BORDERED && x_layout != FATNN_X_BORDERED1) return FATNN_ERR_UNSUPPORTED;
     ConvShape cs;
     int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
     if (rc != FATNN_OK) return rc;
@@ -556,8 +561,8 @@ int fatnn_ternary_conv2d_chain(const void* Wp, const void* Xp, int64_t B, int64_
     ch.relu = relu != 0;
     ch.out_border = out_border;
     ch.Xnext = Xnext;
-    return run_conv(Wp, Xp, FATNN_X_BORDERED, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TERNARY, act_mode, nullptr,
-                    scale, bias, Yf, stream, &ch);
+    return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TERNARY, act_mode, nullptr, scale,
+                    bias, Yf, stream, &ch);
 }
 
 int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int basis, int32_t* C,
@@ -587,7 +592,8 @@ int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int6
 int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
                         int64_t W, int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t* Y,
                         void* stream) {
-    if (x_layout != FATNN_X_PLAIN && x_layout != FATNN_X_BORDERED) return FATNN_ERR_UNSUPPORTED;
+    if (x_layout != FATNN_X_PLAIN && x_layout != FATNN_X_BORDERED && x_layout != FATNN_X_BORDERED1)
+        return FATNN_ERR_UNSUPPORTED;
     ConvShape cs;
     int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
     if (rc != FATNN_OK) return rc;

@@ -93,6 +93,7 @@ struct StreamParams {
     const float* scale;
     const float* bias;
     int32_t B, Hp, Wp, Ho, Wo;
+    int32_t xoff;           // physical border minus the convolution's padding (0 or 1)
     // Layer-chaining epilogue (Xn != nullptr): affine, optional skip and ReLU in fp32, then the
     // next layer's activation quantizer and packing straight into its bordered input buffer.
     plane2* Xn;             // [B][nHp][nWp][nCw] word pairs, ring already initialised

@@ -125,7 +125,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
 
     // byte offset of the first input pixel of the current group's first strip (bordered coordinates)
     auto strip_offset = [&]() {
-        return (uint32_t)b * img_bytes + (uint32_t)(ho * ST) * row_bytes + (uint32_t)(wg * U * ST) * kPixBytes;
+        return (uint32_t)b * img_bytes + (uint32_t)(ho * ST + p.xoff) * row_bytes +
+               (uint32_t)(wg * U * ST + p.xoff) * kPixBytes;
     };
     auto advance = [&]() {
         if (++wg == wgroups) {

@@ -185,3 +185,43 @@ def cfg5_bottleneck(batch: int = 128) -> List[ConvCase]:
         ConvCase("cfg5c_1x1_256to64_56", batch, 256, 56, 56, 64, 1, 1, 1, 0, RELU, config=5, sub=2),
         ConvCase("cfg5c_1x1_64to256_56", batch, 64, 56, 56, 256, 1, 1, 1, 0, RELU, config=5, sub=3),
     ]
+
+
+def trunk_params(batch_seed: int = 0):
+    """Synthetic parameters of the ResNet-18-shaped trunk, as plain numpy arrays.
+
+    Returns a list of blocks; each block is a dict with conv1, conv2 and (for down-sampling blocks)
+    shortcut, each a dict: levels OHWI int8, scale, bias fp32, alpha (a1, a2), stride.  Layer shapes
+    and weight seeds are those of cfg3's layer list.
+    """
+    layers = cfg3(batch=1)
+    blocks_spec = ((64, 64, 1), (64, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2), (256, 256, 1),
+                   (256, 512, 2), (512, 512, 1))
+    out = []
+    li = 0
+
+    def conv(case: "ConvCase", idx: int):
+        lw = levels(rng_for(3, TENSOR_W, idx), (case.Cout, case.R, case.S, case.Cin), case.w_probs)
+        r = rng_for(3, TENSOR_SCALE, idx)
+        scale = (r.uniform(0.5, 1.5, size=case.Cout) / np.sqrt(case.K)).astype(np.float32)
+        bias = (rng_for(3, TENSOR_BIAS, idx).standard_normal(case.Cout) * 0.3).astype(np.float32)
+        alpha = (float(np.float32(0.7 + 0.01 * idx)), float(np.float32(0.9 - 0.01 * idx)))
+        return {"levels": lw, "scale": scale, "bias": bias, "alpha": alpha, "stride": case.stride}
+
+    for cin, cout, stride in blocks_spec:
+        blk = {"conv1": conv(layers[li], li), "conv2": conv(layers[li + 1], li + 1), "shortcut": None}
+        assert layers[li].Cin == cin and layers[li].Cout == cout and layers[li].stride == stride
+        li += 2
+        if stride != 1 or cin != cout:
+            assert layers[li].R == 1 and layers[li].Cin == cin and layers[li].Cout == cout
+            blk["shortcut"] = conv(layers[li], li)
+            li += 1
+        out.append(blk)
+    assert li == len(layers)
+    return out
+
+
+def trunk_input(batch: int, size: int = 56, channels: int = 64) -> np.ndarray:
+    """Non-negative fp32 NHWC input of the trunk (what a ReLU after the stem would produce)."""
+    r = rng_for(3, TENSOR_A, 999)
+    return np.abs(r.standard_normal((batch, size, size, channels))).astype(np.float32)

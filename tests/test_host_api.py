@@ -183,7 +183,7 @@ def test_conv_argument_errors(lib):
     assert call(R=1, S=1, pad=1) == E_UNSUP
     assert call(Cin=48) == E_UNSUP
     assert call(mode=7) == E_UNSUP
-    assert call(xl=2) == E_UNSUP
+    assert call(xl=3) == E_UNSUP
     assert call(H=1, W=1, pad=0) == E_SHAPE            # filter larger than the padded image
     assert call(Y=None) == E_NULL
     assert call(Y=None, Yf=FAKE) == E_NULL             # fp32 output without scale
