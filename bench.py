@@ -43,7 +43,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg3", "quantpack"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -130,6 +130,102 @@ def cpu_baseline_gemm(case, rows=64):
             "kind": "oracle", "sample": f"first {rows} of {case.M} weight rows against all columns, {dt:.2f} s"}
 
 
+def side_workload(args, torch, fatnn, si, dev):
+    """Workloads beyond the headline ones: the chained ResNet-18-shaped trunk (cfg3 as one pipeline) and
+    the HBM-bound quantize-and-pack pass.  Same JSON shape, one line."""
+    import numpy as np
+    if args.workload == "cfg3":
+        from paper_2008_05101_amd import resnet_trunk as rt
+        batch = 64
+        blocks_np = si.trunk_params()
+
+        def cv(d):
+            t = lambda a: torch.from_numpy(a).to(dev)
+            return rt.ConvParams(t(d["levels"]), t(d["scale"]), t(d["bias"]), d["alpha"], d["stride"])
+        blocks = [rt.BlockParams(cv(b["conv1"]), cv(b["conv2"]), None if b["shortcut"] is None else cv(b["shortcut"]))
+                  for b in blocks_np]
+        trunk = rt.Trunk(blocks, batch, 56, (0.6, 0.7), device=str(dev))
+        x = torch.from_numpy(si.trunk_input(batch)).to(dev)
+        for _ in range(args.warmup):
+            trunk.forward(x)
+        torch.cuda.synchronize()
+        steps = args.steps
+        hev = HipEvents(2 * 19 * steps)
+        cur = [0]
+
+        def hook(layer):
+            i = cur[0] * 19 + layer
+            fatnn.time_next_launch(hev.handle(2 * i), hev.handle(2 * i + 1))
+        t0 = time.perf_counter()
+        for s_ in range(steps):
+            cur[0] = s_
+            trunk.forward(x, before_conv=hook)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms_per_step = wall * 1e3 / steps
+        per_layer = [sum(hev.elapsed_ms(2 * (s_ * 19 + l), 2 * (s_ * 19 + l) + 1) for s_ in range(steps)) / steps
+                     for l in range(19)]
+        hev.close()
+        ops = 2.0 * trunk.macs
+        kernel_ms = sum(per_layer)
+        layers = si.cfg3(batch)
+        achieved = ops / (kernel_ms * 1e-3) / 1e12
+        line = {
+            "metric": "ternary GEMM Tops/s (2MNK) at 1 MI355X", "value": round(ops / (ms_per_step * 1e-3) / 1e12, 3),
+            "unit": "Tops/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+            "config": {"workload": "cfg3: the 19 ternary conv layers of a ResNet-18 shape at batch 64 as ONE chained "
+                                   "pipeline (quantize+pack the fp32 input, every conv writes the next layer's packed "
+                                   "input through the fused affine/skip/ReLU/quantize epilogue)", "batch": batch,
+                       "macs": trunk.macs},
+            "roofline": {"bound": "alu", "kernel": "stream_conv_kernel (all 19 launches)", "achieved": round(achieved, 2),
+                         "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s",
+                         "frac": round(achieved / TERNARY_PEAK_TOPS, 4), "traffic": None,
+                         "kernel_ms": round(kernel_ms, 5)},
+            "cpu_baseline": None,
+            "extra": {"per_layer_us": {l.name: round(t * 1e3, 2) for l, t in zip(layers, per_layer)},
+                      "per_layer_tops": {l.name: round(2.0 * l.macs() / (t * 1e-3) / 1e12, 1)
+                                         for l, t in zip(layers, per_layer)}},
+        }
+        print(json.dumps(line))
+        return
+    # quantize-and-pack: fp32 NHWC activations of the 256-channel bottleneck input (128 x 56 x 56 x 256)
+    B, H, W, C = 128, 56, 56, 256
+    x = torch.randn((B, H, W, C), device=dev).abs_()
+    out = torch.empty(fatnn.bordered_act_bytes(B, H, W, C, 0), dtype=torch.uint8, device=dev)
+    lv = torch.randint(0, 3, (B, H, W, C), dtype=torch.int8, device=dev)
+    f1 = lambda: fatnn.quantize_pack_bordered(x, 0, fatnn.RELU, 0.7, 0.9, out=out)
+    f2 = lambda: fatnn.pack_ternary_bordered(lv, 0, fatnn.RELU, out=out)
+    for _ in range(args.warmup):
+        f1()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        f1()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    k1 = time_kernel_ms(torch, f1, 20, 3)
+    k2 = time_kernel_ms(torch, f2, 20, 3)
+    n = B * H * W * C
+    line = {
+        "metric": "quantize-and-pack GB/s at 1 MI355X", "value": round(n * 4.25 / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32 in, u32 bit-planes out",
+        "data": "synthetic",
+        "config": {"workload": "quantize-and-pack of fp32 NHWC activations 128x56x56x256 (Eq. 10 thresholds), "
+                               "4 B read + 0.25 B written per element", "elements": n},
+        "roofline": {"bound": "hbm", "kernel": "quantize_pack_bordered_kernel",
+                     "achieved": round(n * 4.25 / (k1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(n * 4.25 / (k1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel_ms": round(k1, 5)},
+        "cpu_baseline": None,
+        "extra": {"pack_from_int8_levels_ms": round(k2, 5),
+                  "pack_from_int8_levels_GBps": round(n * 1.25 / (k2 * 1e-3) / 1e9, 1)},
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -159,6 +255,9 @@ def main():
         return
 
     extra = {}
+    if args.workload in ("cfg3", "quantpack"):
+        side_workload(args, torch, fatnn, si, dev)
+        return
     if args.workload == "cfg2":
         case = si.cfg2()
         Lw, Lx = case.make()

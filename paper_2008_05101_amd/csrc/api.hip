@@ -192,11 +192,16 @@ int stream_ranges(int64_t M, int64_t ngroups, int64_t group_size, int64_t Kw, in
     int64_t occ = 512 / vgprs;
     if (occ > 8) occ = 8;
     if (occ < 1) occ = 1;
-    int64_t wps = (ngroups * group_size * mblocks + 1024 * 16 - 1) / (1024 * 16);
+    // as many wavefronts per SIMD as the registers allow (up to 6: more only adds weight-load
+    // traffic at the start), but at least three pixel groups per wavefront
+    int64_t wps = occ < 6 ? occ : 6;
+    while (wps > 1 && ngroups * mblocks < 3 * 1024 * wps) --wps;
+    (void)group_size;
     const char* e = getenv("FATNN_STREAM_WPS");
-    if (e != nullptr && atoi(e) > 0) wps = atoi(e);
-    if (wps > occ) wps = occ;
-    if (wps < 1) wps = 1;
+    if (e != nullptr && atoi(e) > 0) {
+        wps = atoi(e);
+        if (wps > occ) wps = occ;
+    }
     int64_t ranges = (1024 * wps) / mblocks;
     if (ranges < 1) ranges = 1;
     const int64_t need = (ngroups + max_groups_per_range - 1) / max_groups_per_range;

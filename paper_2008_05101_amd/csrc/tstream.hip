@@ -308,7 +308,7 @@ int launch_inst(const StreamParams& p, int ranges, hipStream_t stream) {
 
 // Output pixels per group for a filter size / channel-word count / stride.
 constexpr int group_u(int R, int CW, int ST) {
-    if (R == 3) return (ST == 1) ? (CW == 2 ? 6 : 4) : (CW >= 8 ? 2 : 4);
+    if (R == 3) return (ST == 1) ? (CW == 2 ? 8 : 4) : (CW >= 8 ? 2 : 4);
     return (CW >= 8) ? 4 : (CW == 4 ? 4 : 8);   // 1x1
 }
 // Channel words kept in registers per pass: everything, except for 3x3 filters over 512 channels.
