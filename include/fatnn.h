@@ -67,7 +67,7 @@ enum {                                                    /* layout of a level t
     FATNN_NCHW = 4        /* dims = {B, C, H, W}: same packed result as NHWC (gathering, slow path)   */
 };
 enum { FATNN_X_PLAIN = 0, FATNN_X_BORDERED = 1, FATNN_X_BORDERED1 = 2 };  /* packed conv activations */
-enum { FATNN_BASIS_TERNARY = 0, FATNN_BASIS_UNIFORM = 1 };/* two-bit basis, see fatnn_twobit_gemm     */
+enum { FATNN_BASIS_TERNARY = 0, FATNN_BASIS_UNIFORM = 1, FATNN_BASIS_XNOR_ONLY = 2 };  /* see fatnn_twobit_gemm */
 
 /* Largest supported extents: rows, columns < 2^31; K <= 2^24 (keeps |C| <= 2K exact in fp32 too). */
 #define FATNN_MAX_K (1 << 24)
@@ -214,6 +214,10 @@ int fatnn_ternary_conv2d_chain(const void *Wp, const void *Xp, int x_layout, int
  *   FATNN_BASIS_TERNARY  alpha = (1/2, 1/2): 00,01,10,11 -> -1,0,0,+1 (Table 1's codec)
  *   FATNN_BASIS_UNIFORM  alpha = (1, 2):     00,01,10,11 -> -3,-1,+1,+3
  * C[m][n] = sum_k value(w) * value(a), int32.
+ *   FATNN_BASIS_XNOR_ONLY  is not a basis but the ablation of the paper's Table 4: on Table 1's
+ *       codecs it evaluates Eq. 3 with the xnor rule of Eq. 4 ALONE, C = popcount(xnor) - K, i.e.
+ *       without the "extra bit operations" of Eq. 5-7.  It is wrong whenever a weight is 0 (it
+ *       treats 0 * a as the value of a's codec xnor 01) and exists only to time those operations.
  */
 int fatnn_pack_twobit(const int8_t *codes, int layout, const int64_t dims[4], int role, void *packed,
                       size_t packed_bytes, int32_t *n_invalid, void *stream);
@@ -226,6 +230,20 @@ int fatnn_pack_twobit_bordered(const int8_t *codes, const int64_t dims[4], int b
 int fatnn_twobit_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B, int64_t Cin, int64_t H,
                         int64_t W, int64_t Cout, int R, int S, int stride, int pad, int basis, int32_t *Y,
                         void *stream);
+
+/*
+ * Binary networks (Eq. 1): x . y = 2 * popcount(xnor(x, y)) - N for x, y in {-1,+1}^N, one bit per
+ * element (0 stands for -1).  The paper times binary layers next to ternary and 2-bit ones
+ * (Table 3, Tables S1-S2); this is that comparison kernel, on the same tiling.
+ *   bits    device int8 [rows][K] with values 0 / 1 (others are counted in *n_invalid and packed as 0)
+ *   packed  [rows][ceil(K/64)] word pairs, 64 elements per pair, fatnn_binary_packed_bytes() bytes
+ *   C       int32 [M][ldc]
+ */
+size_t fatnn_binary_packed_bytes(int64_t rows, int64_t K);
+int fatnn_pack_binary(const int8_t *bits, int64_t rows, int64_t K, void *packed, size_t packed_bytes,
+                      int32_t *n_invalid, void *stream);
+int fatnn_binary_gemm(const void *Wb, const void *Ab, int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
+                      void *stream);
 
 /*
  * Measurement hook (no paper passage: it serves the roofline report).  The next

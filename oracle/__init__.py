@@ -43,6 +43,7 @@ def _load() -> ctypes.CDLL:
         lib.oracle_ternary_gemm.argtypes = [i8p, i8p, i64, i64, i64, ctypes.c_int, i32p]
         lib.oracle_ternary_conv2d.argtypes = [i8p, i8p] + [i64] * 9 + [ctypes.c_int, i32p]
         lib.oracle_twobit_gemm.argtypes = [i8p, i8p, i64, i64, i64, ctypes.c_int, i32p]
+        lib.oracle_binary_gemm.argtypes = [i8p, i8p, i64, i64, i64, i32p]
         lib.oracle_scale_epilogue.argtypes = [i32p, i64, i64, ctypes.c_int, fp, fp, fp]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -103,6 +104,19 @@ def twobit_gemm(Qw: np.ndarray, Qa: np.ndarray, basis: int = BASIS_TERNARY) -> n
     rc = _load().oracle_twobit_gemm(Qw.ctypes.data, Qa.ctypes.data, M, N, K, basis, C.ctypes.data)
     if rc != 0:
         raise ValueError("code outside {0,1,2,3}")
+    return C
+
+
+def binary_gemm(Bw: np.ndarray, Ba: np.ndarray) -> np.ndarray:
+    """Eq. 1 as the integer dot product of +-1 vectors given as bits 0 / 1."""
+    Bw, Ba = _i8(Bw), _i8(Ba)
+    M, K = Bw.shape
+    N, K2 = Ba.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    C = np.empty((M, N), dtype=np.int32)
+    if _load().oracle_binary_gemm(Bw.ctypes.data, Ba.ctypes.data, M, N, K, C.ctypes.data) != 0:
+        raise ValueError("bit outside {0,1}")
     return C
 
 

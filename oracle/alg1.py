@@ -116,3 +116,24 @@ def gemm_levels(Lw: np.ndarray, La: np.ndarray, act_mode: int = 0) -> np.ndarray
         for n in range(N):
             C[m, n] = inner_product_levels(Lw[m], La[n], act_mode)
     return C
+
+
+def inner_product_xnor_only(x_codecs: Sequence[int], y_codecs: Sequence[int]) -> int:
+    """Eq. 3 with TM replaced by the plain xnor of Eq. 4, i.e. without the zero-operand fix of
+    Eq. 5-7 (the ablation of Table 4).  Wrong exactly on the bold rows of Table 2."""
+    if len(x_codecs) != len(y_codecs):
+        raise ValueError("length mismatch")
+    acc = 0
+    for xc, yc in zip(x_codecs, y_codecs):
+        acc += popcount(~(xc ^ yc) & 0b11)
+    return acc - len(x_codecs)
+
+
+def gemm_xnor_only(Lw: np.ndarray, La: np.ndarray) -> np.ndarray:
+    M, N = Lw.shape[0], La.shape[0]
+    C = np.zeros((M, N), dtype=np.int32)
+    for m in range(M):
+        yw = [codec_of_level(int(v)) for v in Lw[m]]
+        for n in range(N):
+            C[m, n] = inner_product_xnor_only([codec_of_level(int(v)) for v in La[n]], yw)
+    return C

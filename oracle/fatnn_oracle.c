@@ -165,6 +165,25 @@ int oracle_scale_epilogue(const int32_t *C, int64_t rows, int64_t cols, int chan
     return 0;
 }
 
+/* Eq. 1: binary inner product, bits 0 / 1 standing for -1 / +1.  Bw: [M][K], Ba: [N][K]. */
+int oracle_binary_gemm(const int8_t *Bw, const int8_t *Ba, int64_t M, int64_t N, int64_t K, int32_t *C) {
+    int bad = 0;
+    for (int64_t i = 0; i < M * K; ++i)
+        if (Bw[i] != 0 && Bw[i] != 1) bad = 1;
+    for (int64_t i = 0; i < N * K; ++i)
+        if (Ba[i] != 0 && Ba[i] != 1) bad = 1;
+    if (bad) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) acc += (int64_t)((2 * Bw[m * K + k] - 1) * (2 * Ba[n * K + k] - 1));
+            C[m * N + n] = (int32_t)acc;
+        }
+    }
+    return 0;
+}
+
 int oracle_num_threads(void) {
 #ifdef _OPENMP
     extern int omp_get_max_threads(void);

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libfatnn.so")
 WEIGHT, ACT = 0, 1
 SYM, RELU = 0, 1
 ROWMAJOR_K, NHWC, OHWI, OIHW, NCHW = 0, 1, 2, 3, 4
-BASIS_TERNARY, BASIS_UNIFORM = 0, 1
+BASIS_TERNARY, BASIS_UNIFORM, BASIS_XNOR_ONLY = 0, 1, 2
 X_PLAIN, X_BORDERED, X_BORDERED1 = 0, 1, 2
 
 EXPORTS = [
@@ -24,7 +24,8 @@ EXPORTS = [
     "fatnn_pack_ternary_bordered", "fatnn_pack_twobit_bordered", "fatnn_quantize_pack",
     "fatnn_quantize_pack_bordered", "fatnn_bordered_act_init", "fatnn_ternary_conv2d_chain",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
-    "fatnn_twobit_conv2d", "fatnn_time_next_launch", "fatnn_status_str", "fatnn_version",
+    "fatnn_twobit_conv2d", "fatnn_binary_packed_bytes", "fatnn_pack_binary", "fatnn_binary_gemm",
+    "fatnn_time_next_launch", "fatnn_status_str", "fatnn_version",
 ]
 
 
@@ -73,6 +74,10 @@ def lib() -> ctypes.CDLL:
                                                  vp, i32, f32, f32, i32, i32, vp, sz, vp, vp]
         l.fatnn_twobit_gemm.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp]
         l.fatnn_twobit_conv2d.argtypes = [vp, vp, i32, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, vp, vp]
+        l.fatnn_binary_packed_bytes.argtypes = [i64, i64]
+        l.fatnn_binary_packed_bytes.restype = sz
+        l.fatnn_pack_binary.argtypes = [vp, i64, i64, vp, sz, vp, vp]
+        l.fatnn_binary_gemm.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
         l.fatnn_time_next_launch.argtypes = [vp, vp]
         l.fatnn_status_str.argtypes = [i32]
         l.fatnn_status_str.restype = ctypes.c_char_p
@@ -106,6 +111,28 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
     if not t.is_contiguous():
         raise ValueError(f"{what} must be contiguous")
     return t
+
+
+def pack_binary(bits: torch.Tensor, out: Optional[torch.Tensor] = None,
+                n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+    bits = _dev(bits, torch.int8, "bits")
+    rows, K = bits.shape
+    if out is None:
+        out = torch.empty(max(int(lib().fatnn_binary_packed_bytes(rows, K)), 16), dtype=torch.uint8,
+                          device=bits.device)
+    _check(lib().fatnn_pack_binary(_ptr(bits), rows, K, _ptr(out), out.numel(), _ptr(n_invalid), _stream()),
+           "fatnn_pack_binary")
+    return out
+
+
+def binary_gemm(Wb: torch.Tensor, Ab: torch.Tensor, M: int, N: int, K: int,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=Wb.device)
+    ldc = out.stride(0) if out.dim() == 2 and M > 0 else N
+    _check(lib().fatnn_binary_gemm(_ptr(Wb), _ptr(Ab), M, N, K, _ptr(out), max(ldc, N), _stream()),
+           "fatnn_binary_gemm")
+    return out
 
 
 def time_next_launch(start_event: Optional[int], stop_event: Optional[int]) -> None:

@@ -242,6 +242,8 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
             set_ternary_consts(t, Wp, Cout, cs.K, act_mode);
             q.rowc = t.rowc;
             q.cmul = t.cmul;
+        } else {
+            q.cmul = 1;
         }
         q.K = (int32_t)cs.K;
         q.M = (int32_t)Cout;
@@ -270,6 +272,7 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
     p.W = reinterpret_cast<const plane2*>(Wp);
     p.A = reinterpret_cast<const plane2*>(Xp);
     if (op == OP_TERNARY) set_ternary_consts(p, Wp, Cout, cs.K, act_mode);
+    else p.cmul = 1;
     p.K = (int32_t)cs.K;
     p.M = (int32_t)Cout;
     p.N = (int32_t)cs.N;
@@ -574,7 +577,8 @@ int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int6
                       int64_t ldc, void* stream) {
     int rc = check_gemm_dims(M, N, K);
     if (rc != FATNN_OK) return rc;
-    if (basis != FATNN_BASIS_TERNARY && basis != FATNN_BASIS_UNIFORM) return FATNN_ERR_UNSUPPORTED;
+    if (basis != FATNN_BASIS_TERNARY && basis != FATNN_BASIS_UNIFORM && basis != FATNN_BASIS_XNOR_ONLY)
+        return FATNN_ERR_UNSUPPORTED;
     if (basis == FATNN_BASIS_UNIFORM && K > (1 << 20)) return FATNN_ERR_SIZE;   // |C| <= 9K in int32
     if (M == 0 || N == 0) return FATNN_OK;
     if (C == nullptr) return FATNN_ERR_NULL;
@@ -590,7 +594,9 @@ int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int6
     p.Kw = (int32_t)fatnn_words_per_row(K);
     p.C = C; p.ldc_m = ldc; p.ldc_n = 1;
     p.is_conv = 0;
-    const int op = basis == FATNN_BASIS_TERNARY ? OP_TWOBIT_TERNARY : OP_TWOBIT_UNIFORM;
+    const int op = basis == FATNN_BASIS_TERNARY ? OP_TWOBIT_TERNARY
+                                                : (basis == FATNN_BASIS_UNIFORM ? OP_TWOBIT_UNIFORM : OP_XOR_PAIR);
+    p.cmul = 1;   // xnor rule on codecs: K - popcount(xor)
     return launch_gemm(p, op, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
 }
 
@@ -602,13 +608,14 @@ int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B,
     ConvShape cs;
     int rc = check_conv_dims(B, Cin, H, W, Cout, R, S, stride, pad, &cs);
     if (rc != FATNN_OK) return rc;
-    if (basis != FATNN_BASIS_TERNARY) return FATNN_ERR_UNSUPPORTED;
+    if (basis != FATNN_BASIS_TERNARY && basis != FATNN_BASIS_XNOR_ONLY) return FATNN_ERR_UNSUPPORTED;
     if (B == 0 || Cout == 0) return FATNN_OK;
     if (Y == nullptr) return FATNN_ERR_NULL;
     if (Wp == nullptr || Xp == nullptr) return FATNN_ERR_NULL;
     if (!aligned(Wp, 16) || !aligned(Xp, 16) || !aligned(Y, 4)) return FATNN_ERR_ALIGN;
-    return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs, OP_TWOBIT_TERNARY, FATNN_SYM, Y,
-                    nullptr, nullptr, nullptr, stream);
+    return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs,
+                    basis == FATNN_BASIS_TERNARY ? OP_TWOBIT_TERNARY : OP_XOR_PAIR, FATNN_SYM, Y, nullptr, nullptr,
+                    nullptr, stream);
 }
 
 int fatnn_time_next_launch(void* start_event, void* stop_event) {
@@ -616,6 +623,46 @@ int fatnn_time_next_launch(void* start_event, void* stop_event) {
     fatnn::g_timing.start = reinterpret_cast<hipEvent_t>(start_event);
     fatnn::g_timing.stop = reinterpret_cast<hipEvent_t>(stop_event);
     return FATNN_OK;
+}
+
+int fatnn_pack_binary(const int8_t* bits, int64_t rows, int64_t K, void* packed, size_t packed_bytes,
+                      int32_t* n_invalid, void* stream) {
+    if (rows < 0 || K < 1) return FATNN_ERR_SHAPE;
+    if (rows > kMaxRows || K > 2 * (int64_t)FATNN_MAX_K) return FATNN_ERR_SIZE;
+    if (rows == 0) return FATNN_OK;
+    if (bits == nullptr || packed == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(packed, 16) || !aligned(n_invalid, 4)) return FATNN_ERR_ALIGN;
+    if (packed_bytes < fatnn_binary_packed_bytes(rows, K)) return FATNN_ERR_SIZE;
+    return launch_pack_binary(bits, rows, K, reinterpret_cast<plane2*>(packed), n_invalid,
+                              reinterpret_cast<hipStream_t>(stream)) == 0
+               ? FATNN_OK
+               : FATNN_ERR_HIP;
+}
+
+size_t fatnn_binary_packed_bytes(int64_t rows, int64_t K) {
+    if (rows < 0 || K < 1) return 0;
+    return (size_t)rows * (size_t)((K + 63) / 64) * sizeof(plane2);
+}
+
+int fatnn_binary_gemm(const void* Wb, const void* Ab, int64_t M, int64_t N, int64_t K, int32_t* C, int64_t ldc,
+                      void* stream) {
+    if (M < 0 || N < 0 || K < 1) return FATNN_ERR_SHAPE;
+    if (M > kMaxRows || N > kMaxRows || K > 2 * (int64_t)FATNN_MAX_K) return FATNN_ERR_SIZE;
+    if (M == 0 || N == 0) return FATNN_OK;
+    if (C == nullptr || Wb == nullptr || Ab == nullptr) return FATNN_ERR_NULL;
+    if (ldc < N) return FATNN_ERR_SHAPE;
+    if (!aligned(Wb, 16) || !aligned(Ab, 16) || !aligned(C, 4)) return FATNN_ERR_ALIGN;
+    GemmParams p{};
+    p.W = reinterpret_cast<const plane2*>(Wb);
+    p.A = reinterpret_cast<const plane2*>(Ab);
+    p.K = (int32_t)K;
+    p.cmul = 2;   // Eq. 1: 2 * popcount(xnor) - N = N - 2 * popcount(xor)
+    p.M = (int32_t)M;
+    p.N = (int32_t)N;
+    p.Kw = (int32_t)((K + 63) / 64);
+    p.C = C; p.ldc_m = ldc; p.ldc_n = 1;
+    p.is_conv = 0;
+    return launch_gemm(p, OP_XOR_PAIR, reinterpret_cast<hipStream_t>(stream)) == 0 ? FATNN_OK : FATNN_ERR_HIP;
 }
 
 const char* fatnn_status_str(int status) {

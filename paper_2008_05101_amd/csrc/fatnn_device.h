@@ -16,7 +16,8 @@ using plane2 = uint2;
 enum PackKind : int {
     PACK_ACT = 0,      // .x = (l == 2), .y = (l >= 1)
     PACK_WEIGHT = 1,   // .x = (l == 2), .y = (l != 1)
-    PACK_TWOBIT = 2    // .x = bit 1,    .y = bit 0 of a code in {0,1,2,3}
+    PACK_TWOBIT = 2,   // .x = bit 1,    .y = bit 0 of a code in {0,1,2,3}
+    PACK_BINARY = 3    // one bit per element, 64 elements per word pair (.x = first 32)
 };
 
 // Source addressing of a level tensor: element (row, k) lives at
@@ -40,13 +41,16 @@ int launch_quantize_pack_bordered(const float* x, int64_t B, int64_t H, int64_t 
                                   plane2* packed, int32_t* n_invalid, hipStream_t stream);
 int launch_fill_words(plane2* dst, int64_t count, plane2 word, hipStream_t stream);
 int launch_interleave_weights(const plane2* packed, int64_t rows, int64_t Kw, plane2* inter, hipStream_t stream);
+int launch_pack_binary(const int8_t* bits, int64_t rows, int64_t K, plane2* packed, int32_t* n_invalid,
+                       hipStream_t stream);
 int launch_row_constants(const plane2* packed, int64_t rows, int64_t Kw, int32_t* nnz, int32_t* npos,
                          hipStream_t stream);
 
 enum GemmOp : int {
     OP_TERNARY = 0,        // Eq. 3 in its reduced form: 2 logic + 2 popcount per word pair
     OP_TWOBIT_TERNARY = 1, // Eq. 2, alpha = beta = (1/2,1/2): 4 xor + 4 popcount, one accumulator
-    OP_TWOBIT_UNIFORM = 2  // Eq. 2, alpha = beta = (1,2):     4 xor + 4 popcount, three accumulators
+    OP_TWOBIT_UNIFORM = 2, // Eq. 2, alpha = beta = (1,2):     4 xor + 4 popcount, three accumulators
+    OP_XOR_PAIR = 3        // Eq. 1 / Eq. 4 alone: popcount(x ^ y) word by word, C = K - cmul * sum
 };
 
 struct GemmParams {

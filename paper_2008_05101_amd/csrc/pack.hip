@@ -105,6 +105,36 @@ __global__ __launch_bounds__(256) void pack_contiguous_kernel(const int8_t* __re
     }
 }
 
+// One-bit elements (Eq. 1: 0 stands for -1, 1 for +1): 64 per word pair, .x holds the first 32.
+// Values other than 0 / 1 are counted as invalid and packed as 0; tail bits are 0 in both
+// operands, so they cancel in the xor.
+__global__ __launch_bounds__(256) void pack_binary_kernel(const int8_t* __restrict__ bits, int64_t rows, int64_t K,
+                                                          int64_t Kp, plane2* __restrict__ packed,
+                                                          int32_t* __restrict__ n_invalid) {
+    const int64_t total = rows * Kp;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += stride) {
+        const int64_t row = id / Kp;
+        const int64_t kp = id - row * Kp;
+        const int8_t* src = bits + row * K + kp * 64;
+        uint32_t w[2] = {0u, 0u};
+        int bad = 0;
+        for (int e = 0; e < 64; ++e) {
+            const int64_t k = kp * 64 + e;
+            if (k < K) {
+                const int v = src[e];
+                bad += (v != 0 && v != 1) ? 1 : 0;
+                w[e >> 5] |= (uint32_t)(v == 1) << (e & 31);
+            }
+        }
+        plane2 out;
+        out.x = w[0];
+        out.y = w[1];
+        packed[id] = out;
+        if (bad != 0 && n_invalid != nullptr) atomicAdd(n_invalid, bad);
+    }
+}
+
 // General (slow) path for tensors whose K axis is not contiguous (OIHW weights,
 // NCHW activations): one thread still makes one word pair, reading byte by byte.
 template <int KIND>
@@ -365,6 +395,16 @@ int launch_pack_contiguous(const int8_t* levels, int64_t rows, int64_t K, int ki
         default: return -1;
     }
 #undef FATNN_LAUNCH_PACK
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_pack_binary(const int8_t* bits, int64_t rows, int64_t K, plane2* packed, int32_t* n_invalid,
+                       hipStream_t stream) {
+    const int64_t Kp = (K + 63) / 64;
+    const int64_t total = rows * Kp;
+    if (total == 0) return 0;
+    hipLaunchKernelGGL(pack_binary_kernel, dim3(grid_for(total, 256)), dim3(256), 0, stream, bits, rows, K, Kp, packed,
+                       n_invalid);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

@@ -73,8 +73,26 @@ struct Acc<OP_TWOBIT_UNIFORM> {
     }
 };
 
+// Plain xor-popcount over both words of a pair: the binary inner product of Eq. 1 (64 one-bit
+// elements per pair), and the xnor rule of Eq. 4 without the zero-operand fix of Eq. 5-7.
+template <>
+struct Acc<OP_XOR_PAIR> {
+    int32_t v;
+    __device__ __forceinline__ void clear() { v = 0; }
+    __device__ __forceinline__ void step(plane2 w, plane2 a) {
+        popc_acc(v, a.x ^ w.x);
+        popc_acc(v, a.y ^ w.y);
+    }
+};
+
 template <int OP>
 __device__ __forceinline__ int32_t finalize(const Acc<OP>& acc, const GemmParams& p, int32_t rowconst);
+
+template <>
+__device__ __forceinline__ int32_t finalize<OP_XOR_PAIR>(const Acc<OP_XOR_PAIR>& acc, const GemmParams& p, int32_t) {
+    // binary (Eq. 1): 2 * popcount(xnor) - N = N - 2 * popcount(xor);  xnor rule on codecs: N - popcount(xor)
+    return p.K - p.cmul * acc.v;
+}
 
 template <>
 __device__ __forceinline__ int32_t finalize<OP_TERNARY>(const Acc<OP_TERNARY>& acc, const GemmParams&,
@@ -354,6 +372,7 @@ int launch_gemm(const GemmParams& p, int op, hipStream_t stream) {
         case OP_TERNARY: return launch_op<OP_TERNARY, 8, 8>(p, stream);
         case OP_TWOBIT_TERNARY: return launch_op<OP_TWOBIT_TERNARY, 8, 8>(p, stream);
         case OP_TWOBIT_UNIFORM: return launch_op<OP_TWOBIT_UNIFORM, 8, 4>(p, stream);
+        case OP_XOR_PAIR: return launch_op<OP_XOR_PAIR, 8, 8>(p, stream);
         default: return -3;
     }
 }

@@ -165,6 +165,9 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
                     if (OP == OP_TERNARY) {
                         popc_acc(acc[u], (xh ^ ww.x) & ww.y);
                         popc_acc(acc[u], (xl ^ ww.x) & ww.y);
+                    } else if (OP == OP_XOR_PAIR) {
+                        popc_acc(acc[u], xh ^ ww.x);
+                        popc_acc(acc[u], xl ^ ww.y);
                     } else {
                         popc_acc(acc[u], xh ^ ww.x);
                         popc_acc(acc[u], xh ^ ww.y);
@@ -227,7 +230,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (wo0 + u >= p.Wo) break;
-                const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : p.K - (acc[u] >> 1);
+                const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : (OP == OP_XOR_PAIR ? p.K - p.cmul * acc[u] : p.K - (acc[u] >> 1));
                 float f = sc * (float)v;
                 if (p.bias != nullptr) f = f + bs;
                 const int64_t o = (n0 + u) * p.ldc_n + m;
@@ -250,7 +253,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (wo0 + u < p.Wo && m_ok) {
-                const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : p.K - (acc[u] >> 1);
+                const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : (OP == OP_XOR_PAIR ? p.K - p.cmul * acc[u] : p.K - (acc[u] >> 1));
                 const int64_t o = (n0 + u) * p.ldc_n + m;
                 // outputs are written once and not read again by this kernel: stream them out
                 if (p.C != nullptr) __builtin_nontemporal_store(v, &p.C[o]);
@@ -325,7 +328,7 @@ int stream_max_groups_per_range(int R, int Cw, int stride) {
 }
 
 bool stream_supported(int op, int R, int S, int Cw, int stride) {
-    if (op != OP_TERNARY && op != OP_TWOBIT_TERNARY) return false;
+    if (op != OP_TERNARY && op != OP_TWOBIT_TERNARY && op != OP_XOR_PAIR) return false;
     if (R != S || (stride != 1 && stride != 2)) return false;
     if (R == 3) return Cw == 2 || Cw == 4 || Cw == 8 || Cw == 16;
     if (R == 1) return Cw == 2 || Cw == 4 || Cw == 8 || Cw == 16;
@@ -337,8 +340,9 @@ int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride,
     if (R == RR && Cw == CC && stride == SS) {                                                                 \
         constexpr int UU = group_u(RR, CC, SS);                                                                \
         constexpr int RC = resident_cw(RR, CC);                                                                \
-        return op == OP_TERNARY ? launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream)               \
-                                : launch_inst<OP_TWOBIT_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream);       \
+        if (op == OP_TERNARY) return launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream);          \
+        if (op == OP_XOR_PAIR) return launch_inst<OP_XOR_PAIR, RR, RC, CC, SS, UU>(p, ranges, stream);        \
+        return launch_inst<OP_TWOBIT_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream);                          \
     }
     FATNN_STREAM_CASE(3, 2, 1)
     FATNN_STREAM_CASE(3, 4, 1)

@@ -160,10 +160,54 @@ def test_gemm_argument_errors(lib):
     assert f(None, None, 0, 4, 8, 0, None, 4, None, None, None, 0, None) == OK          # empty problem
     assert f(None, None, 4, 0, 8, 0, None, 0, None, None, None, 0, None) == OK
     g = lib.fatnn_twobit_gemm
-    assert g(*a, 4, 4, 8, 2, FAKE, 4, None) == E_UNSUP
+    assert g(*a, 4, 4, 8, 7, FAKE, 4, None) == E_UNSUP
     assert g(*a, 4, 4, 8, 0, None, 4, None) == E_NULL
     assert g(*a, 4, 4, 8, 0, FAKE, 2, None) == E_SHAPE
     assert g(*a, 4, 4, (1 << 20) + 1, 1, FAKE, 4, None) == E_SIZE                     # 9K must fit int32
+
+
+def test_binary_argument_errors(lib):
+    f = lib.fatnn_pack_binary
+    assert lib.fatnn_binary_packed_bytes(3, 65) == 3 * 2 * 8
+    assert lib.fatnn_binary_packed_bytes(3, 0) == 0
+    assert f(FAKE, 4, 0, FAKE, 1 << 20, None, None) == E_SHAPE
+    assert f(None, 4, 8, FAKE, 1 << 20, None, None) == E_NULL
+    assert f(FAKE, 4, 8, FAKE + 4, 1 << 20, None, None) == E_ALIGN
+    assert f(FAKE, 4, 8, FAKE, 8, None, None) == E_SIZE
+    assert f(None, 0, 8, None, 0, None, None) == OK
+    g = lib.fatnn_binary_gemm
+    assert g(FAKE, FAKE, 4, 4, 0, FAKE, 4, None) == E_SHAPE
+    assert g(FAKE, FAKE, 4, 4, 8, None, 4, None) == E_NULL
+    assert g(FAKE, FAKE, 4, 4, 8, FAKE, 3, None) == E_SHAPE
+    assert g(FAKE, FAKE + 8, 4, 4, 8, FAKE, 4, None) == E_ALIGN
+    assert g(None, None, 0, 4, 8, None, 4, None) == OK
+
+
+def test_chain_argument_errors(lib):
+    f = lib.fatnn_ternary_conv2d_chain
+    f.argtypes = ([ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int] + [ctypes.c_int64] * 5 + [ctypes.c_int] * 5 +
+                  [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_float, ctypes.c_float, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p])
+
+    def call(xl=1, Cin=64, Cout=64, R=3, S=3, stride=1, pad=1, scale=FAKE, a1=1.0, a2=1.0, om=1, ob=1, Xn=FAKE,
+             nbytes=1 << 30):
+        return f(FAKE, FAKE, xl, 2, Cin, 8, 8, Cout, R, S, stride, pad, 1, scale, None, None, 1, a1, a2, om, ob, Xn,
+                 nbytes, None, None)
+
+    assert call(xl=0) == E_UNSUP              # needs a bordered input
+    assert call(Cin=96) == E_UNSUP            # no streaming kernel for 3 channel words
+    assert call(Cout=48) == E_UNSUP
+    assert call(ob=2) == E_UNSUP
+    assert call(om=4) == E_UNSUP
+    assert call(a1=0.0) == E_SHAPE
+    assert call(scale=None) == E_NULL
+    assert call(Xn=None) == E_NULL
+    assert call(nbytes=64) == E_SIZE
+    g = lib.fatnn_bordered_act_init
+    assert g(None, 1 << 20, 2, 4, 4, 64, 1, 0, None) == E_NULL
+    assert g(FAKE, 16, 2, 4, 4, 64, 1, 0, None) == E_SIZE
+    assert g(FAKE, 1 << 20, 2, 4, 4, 48, 1, 0, None) == E_UNSUP
+    assert g(FAKE, 1 << 20, 2, 4, 4, 64, 1, 5, None) == E_UNSUP
 
 
 def test_conv_argument_errors(lib):

@@ -268,3 +268,37 @@ def test_scale_epilogue():
     # against exact arithmetic: one multiply is correctly rounded
     exact = scale.astype(np.float64)[:, None] * C.astype(np.float64)
     assert np.array_equal(oracle.scale_epilogue(C, scale, None, True), exact.astype(np.float32))
+
+
+# --------------------------------------------------------------------------- Eq. 1 and the xnor-only ablation
+def test_binary_oracle_eq1():
+    rnd = np.random.default_rng(31)
+    K = 131
+    Bw = rnd.integers(0, 2, size=(6, K), dtype=np.int8)
+    Ba = rnd.integers(0, 2, size=(7, K), dtype=np.int8)
+    C = oracle.binary_gemm(Bw, Ba)
+    # Eq. 1 written with popcounts: 2 * popcount(xnor) - N
+    xnor_pop = K - (Bw[:, None, :] ^ Ba[None, :, :]).sum(axis=2)
+    assert np.array_equal(C, 2 * xnor_pop - K)
+    assert (oracle.binary_gemm(Bw, Bw).diagonal() == K).all()
+    assert (oracle.binary_gemm(Bw, (1 - Bw).astype(np.int8)).diagonal() == -K).all()
+    with pytest.raises(ValueError):
+        oracle.binary_gemm(np.array([[2]], np.int8), np.array([[1]], np.int8))
+
+
+def test_xnor_only_is_wrong_exactly_where_both_operands_are_zero():
+    # Table 2's bold rows: plain xnor fails only for 0 * 0.  With 0 spelled 01 in both operands the
+    # error is +1 per such pair, so the ablated inner product = true product + #(both zero).
+    rnd = np.random.default_rng(32)
+    Lw = rnd.integers(0, 3, size=(5, 67), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(6, 67), dtype=np.int8)
+    got = alg1.gemm_xnor_only(Lw, La)
+    both_zero = (Lw == 1).astype(np.int64) @ (La == 1).astype(np.int64).T
+    assert np.array_equal(got, oracle.ternary_gemm(Lw, La, 0) + both_zero)
+    # per codec pair, against Table 2's value column
+    for xc in range(4):
+        for yc in range(4):
+            true = alg1.decode_field(xc) * alg1.decode_field(yc)
+            z = alg1.inner_product_xnor_only([xc], [yc])
+            exception = alg1.decode_field(xc) == 0 and alg1.decode_field(yc) == 0
+            assert (z != true) == exception
