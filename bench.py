@@ -43,7 +43,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg3", "quantpack"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg3", "cfg5", "quantpack"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -190,6 +190,71 @@ def side_workload(args, torch, fatnn, si, dev):
         }
         print(json.dumps(line))
         return
+    if args.workload == "cfg5":
+        # ragged and low-K shapes, packing of the activations included in every step
+        results = {}
+        total_ms = 0.0
+        total_ops = 0.0
+        worst = None
+        for case in (si.cfg5_ragged(), si.cfg5_gemv()):
+            Lw, La = case.make()
+            Lw_d, La_d = torch.from_numpy(Lw).to(dev), torch.from_numpy(La).to(dev)
+            Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT)
+            Ap = torch.empty(max(fatnn.packed_bytes(fatnn.ACT, case.N, case.K), 16), dtype=torch.uint8, device=dev)
+            C = torch.empty((case.M, case.N), dtype=torch.int32, device=dev)
+
+            def step(La_d=La_d, Ap=Ap, Wp=Wp, C=C, case=case):
+                fatnn.pack_ternary(La_d, fatnn.ACT, out=Ap)
+                fatnn.ternary_gemm(Wp, Ap, case.M, case.N, case.K, case.act_mode, out=C)
+            ms = time_kernel_ms(torch, step, args.steps, args.warmup)
+            kms = time_kernel_ms(torch, lambda: fatnn.ternary_gemm(Wp, Ap, case.M, case.N, case.K, case.act_mode, out=C),
+                                 args.steps, args.warmup)
+            Kw = (case.K + 31) // 32
+            nbytes = case.N * case.K + 2 * case.N * Kw * 8 + case.M * Kw * 8 + case.M * case.N * 4
+            results[case.name] = {"step_us": round(ms * 1e3, 2), "gemm_us": round(kms * 1e3, 2),
+                                  "tops": round(2.0 * case.macs() / (ms * 1e-3) / 1e12, 2),
+                                  "compulsory_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+            total_ms += ms
+            total_ops += 2.0 * case.macs()
+        for case in si.cfg5_bottleneck():
+            Lw, Lx = case.make()
+            Lw_d, Lx_d = torch.from_numpy(Lw).to(dev), torch.from_numpy(Lx).to(dev)
+            Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT, fatnn.OHWI)
+            Xp = torch.empty(fatnn.bordered_act_bytes(case.B, case.H, case.W, case.Cin, 0), dtype=torch.uint8, device=dev)
+            Y = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.int32, device=dev)
+            cargs = (case.B, case.Cin, case.H, case.W, case.Cout, 1, 1, 1, 0, case.act_mode)
+
+            def step(Lx_d=Lx_d, Xp=Xp, Wp=Wp, Y=Y, cargs=cargs, case=case):
+                fatnn.pack_ternary_bordered(Lx_d, 0, case.act_mode, out=Xp)
+                fatnn.ternary_conv2d(Wp, Xp, *cargs, out=Y, x_layout=fatnn.X_BORDERED)
+            ms = time_kernel_ms(torch, step, args.steps, args.warmup)
+            kms = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *cargs, out=Y, x_layout=fatnn.X_BORDERED),
+                                 args.steps, args.warmup)
+            npix = case.B * case.H * case.W
+            # int8 levels read + packed words written and read back + int32 output written
+            nbytes = npix * case.Cin + 2 * npix * case.Cin // 4 + npix * case.Cout * 4
+            results[case.name] = {"step_us": round(ms * 1e3, 2), "conv_us": round(kms * 1e3, 2),
+                                  "tops": round(2.0 * case.macs() / (ms * 1e-3) / 1e12, 2),
+                                  "compulsory_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                  "conv_GBps": round((npix * case.Cin // 4 + npix * case.Cout * 4) / (kms * 1e-3) / 1e9, 1)}
+            total_ms += ms
+            total_ops += 2.0 * case.macs()
+            if worst is None or results[case.name]["conv_GBps"] > worst[1]:
+                worst = (case.name, results[case.name]["conv_GBps"], kms)
+        line = {
+            "metric": "ternary GEMM Tops/s (2MNK) at 1 MI355X", "value": round(total_ops / (total_ms * 1e-3) / 1e12, 3),
+            "unit": "Tops/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(total_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+            "config": {"workload": "cfg5: ragged GEMM 512x3136x4609, GEMV 4096x1x4608, 1x1 convs 256->64 and 64->256 "
+                                   "@56x56 batch 128; every step packs its activations first"},
+            "roofline": {"bound": "hbm", "kernel": f"stream_conv_kernel on {worst[0]}", "achieved": worst[1],
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(worst[1] / HBM_PEAK_GBS, 4),
+                         "traffic": None, "kernel_ms": round(worst[2], 5)},
+            "cpu_baseline": None, "extra": results,
+        }
+        print(json.dumps(line))
+        return
     # quantize-and-pack: fp32 NHWC activations of the 256-channel bottleneck input (128 x 56 x 56 x 256)
     B, H, W, C = 128, 56, 56, 256
     x = torch.randn((B, H, W, C), device=dev).abs_()
@@ -255,7 +320,7 @@ def main():
         return
 
     extra = {}
-    if args.workload in ("cfg3", "quantpack"):
+    if args.workload in ("cfg3", "cfg5", "quantpack"):
         side_workload(args, torch, fatnn, si, dev)
         return
     if args.workload == "cfg2":
@@ -352,9 +417,14 @@ def main():
                                                                        x_layout=fatnn.X_BORDERED), 50, 5)
                 t3 = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y,
                                                                         x_layout=fatnn.X_BORDERED), 50, 5)
+                t4 = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *conv_args[:-1], fatnn.BASIS_XNOR_ONLY,
+                                                                       out=Y, x_layout=fatnn.X_BORDERED), 50, 5)
                 extra["twobit_conv_ms"] = round(t2, 5)
                 extra["ternary_conv_int32_only_ms"] = round(t3, 5)
                 extra["speedup_vs_twobit"] = round(t2 / t3, 3)
+                # Table 4's ablation: the same layer with the xnor rule alone (no zero-operand fix)
+                extra["xnor_only_conv_ms"] = round(t4, 5)
+                extra["extra_bit_ops_cost"] = round((t3 - t4) / t3, 4)
                 # the large-GEMM roofline point
                 g = si.cfg4()
                 Gw = torch.randint(0, 3, (g.M, g.K), dtype=torch.int8, device=dev)
@@ -366,11 +436,17 @@ def main():
                 G2w = fatnn.pack_twobit(code[Gw.long()])
                 G2a = fatnn.pack_twobit(code[Ga.long()])
                 tg2 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(G2w, G2a, g.M, g.N, g.K, 0, out=Gc), 10, 2)
+                tg3 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(G2w, G2a, g.M, g.N, g.K, 2, out=Gc), 10, 2)
+                Bw = fatnn.pack_binary(torch.randint(0, 2, (g.M, g.K), dtype=torch.int8, device=dev))
+                Ba = fatnn.pack_binary(torch.randint(0, 2, (g.N, g.K), dtype=torch.int8, device=dev))
+                tb = time_kernel_ms(torch, lambda: fatnn.binary_gemm(Bw, Ba, g.M, g.N, g.K, out=Gc), 10, 2)
                 gt = 2.0 * g.macs() / (tg * 1e-3) / 1e12
                 extra["gemm8192"] = {"ternary_ms": round(tg, 4), "ternary_tops": round(gt, 1),
                                      "frac_of_alu_peak": round(gt / TERNARY_PEAK_TOPS, 4),
-                                     "twobit_ms": round(tg2, 4), "speedup_vs_twobit": round(tg2 / tg, 3)}
-                del Gw, Ga, Gwp, Gap, Gc, G2w, G2a
+                                     "twobit_ms": round(tg2, 4), "speedup_vs_twobit": round(tg2 / tg, 3),
+                                     "binary_ms": round(tb, 4), "ternary_over_binary": round(tg / tb, 3),
+                                     "xnor_only_ms": round(tg3, 4), "extra_bit_ops_cost": round((tg - tg3) / tg, 4)}
+                del Gw, Ga, Gwp, Gap, Gc, G2w, G2a, Bw, Ba
                 # int8 MFMA comparison point (context only): same operands as int8 values through the BLAS
                 try:
                     a8 = (Lw_d.reshape(case.Cout, -1) - 1).contiguous()

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfatnn.so")
-SOURCES = ["api.hip", "pack.hip", "tgemm.hip", "tstream.hip"]
+SOURCES = ["api.hip", "pack.hip", "tgemm.hip", "tgemv.hip", "tstream.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -73,6 +73,8 @@ struct GemmParams {
 };
 
 int launch_gemm(const GemmParams& p, int op, hipStream_t stream);
+bool skinny_supported(const GemmParams& p, int op);          // N <= 8 ternary GEMM (matrix-vector shaped)
+int launch_skinny_gemm(const GemmParams& p, hipStream_t stream);
 
 // Measurement hook (fatnn_time_next_launch): events that the next GEMM / convolution
 // kernel launch of this thread attaches to the dispatch itself; consumed by that launch.

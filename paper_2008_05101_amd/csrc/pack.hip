@@ -77,6 +77,13 @@ __global__ __launch_bounds__(256) void pack_contiguous_kernel(const int8_t* __re
             }
             d[0] = a.x; d[1] = a.y; d[2] = a.z; d[3] = a.w;
             d[4] = b.x; d[5] = b.y; d[6] = b.z; d[7] = b.w;
+        } else if (k0 + 32 <= K) {
+            // rows do not start on a 16-byte boundary: byte-aligned dword loads (global memory
+            // accesses need no natural alignment on this target)
+            typedef uint32_t __attribute__((aligned(1))) unaligned_u32;
+            const unaligned_u32* s1 = reinterpret_cast<const unaligned_u32*>(src);
+#pragma unroll
+            for (int w = 0; w < 8; ++w) d[w] = s1[w];
         } else {
             const uint32_t fill = tail_fill<KIND>() & 0xFFu;
 #pragma unroll

@@ -359,6 +359,9 @@ template <int OP, int TM, int TN>
 int launch_op(const GemmParams& p, hipStream_t stream) {
     constexpr int WTM = 8 * TM, WTN = 8 * TN;
     const int64_t wave_tiles = (((int64_t)p.M + WTM - 1) / WTM) * (((int64_t)p.N + WTN - 1) / WTN);
+    // fewer 64x64 wavefront tiles than SIMDs: quarter-size register tiles, four wavefronts per
+    // 64x64 workgroup tile, so that four times as many wavefronts share the work
+    if (wave_tiles < 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
     if (wave_tiles < 4 * 1024) return launch_shape<OP, 1, 1, TM, TN>(p, stream);
     if (p.M <= WTM) return launch_shape<OP, 1, 4, TM, TN>(p, stream);
     return launch_shape<OP, 2, 2, TM, TN>(p, stream);
@@ -368,6 +371,7 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
 
 int launch_gemm(const GemmParams& p, int op, hipStream_t stream) {
     if (p.M == 0 || p.N == 0) return 0;
+    if (skinny_supported(p, op)) return launch_skinny_gemm(p, stream);
     switch (op) {
         case OP_TERNARY: return launch_op<OP_TERNARY, 8, 8>(p, stream);
         case OP_TWOBIT_TERNARY: return launch_op<OP_TWOBIT_TERNARY, 8, 8>(p, stream);

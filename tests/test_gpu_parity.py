@@ -127,6 +127,33 @@ def test_gemm_parity_small_and_ragged(M, N, K, mode):
     assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, mode))
 
 
+@pytest.mark.parametrize("M,N,K", [(2048, 2100, 96), (64, 70000, 64), (2100, 1100, 130), (4096, 8, 300)])
+def test_gemm_parity_every_workgroup_shape(M, N, K):
+    # enough 64x64 tiles for the one-wavefront, the 64x256 and the 128x128 workgroup shapes
+    rnd = np.random.default_rng(M + N + K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    C, _ = gemm_gpu(Lw, La, 1)
+    assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, 1))
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 7, 8])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_skinny_gemm_parity(N, mode):
+    rnd = np.random.default_rng(N * 3 + mode)
+    for M, K in [(1, 1), (5, 33), (130, 4609), (1027, 200)]:
+        Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+        La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+        scale = si.scale_vec(rnd, M)
+        bias = si.bias_vec(rnd, M)
+        big = torch.full((M, N + 3), -5, dtype=torch.int32, device=DEV)
+        C, Cf = gemm_gpu(Lw, La, mode, out=big[:, :N], scale=dev(scale), bias=dev(bias))
+        want = oracle.ternary_gemm(Lw, La, mode)
+        assert np.array_equal(C.cpu().numpy(), want)
+        assert (big[:, N:] == -5).all()
+        assert np.array_equal(Cf.cpu().numpy(), oracle.scale_epilogue(want, scale, bias, True))
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_gemm_cfg1(mode):
     case = si.cfg1()
