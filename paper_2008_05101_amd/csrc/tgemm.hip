@@ -277,29 +277,21 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
         // Fragments of k-word j+1 are read from LDS while k-word j is consumed.  The
         // scheduling fences keep the compiler from hoisting every LDS read of the stage
         // to its top (which needs more registers than there are).
-        if (p.Kw - kt * KT >= KT) {
+        {
+            // jn = k-words of this stage that exist (all KT except in the last, partial stage);
+            // the per-word test is a scalar branch
+            const int jn = p.Kw - kt * KT;
             plane2 w[2][TM], a[2][TN];
             read_frag(buf, 0, w[0], a[0]);
 #pragma unroll
             for (int j = 0; j < KT; ++j) {
-                if (j + 1 < KT) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+                if (j >= jn) break;
+                if (j + 1 < KT && j + 1 < jn) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
                 __builtin_amdgcn_sched_barrier(0);
-            }
-        } else {
-            // last, partial stage: only the k-words that exist
-            const int jn = p.Kw - kt * KT;
-#pragma unroll 1
-            for (int j = 0; j < jn; ++j) {
-                plane2 w[TM], a[TN];
-                read_frag(buf, j, w, a);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[i], a[c]);
             }
         }
         if (kt + 1 < nkt) stage(buf ^ 1);

@@ -57,3 +57,21 @@ def test_trunk_matches_oracle_pipeline(batch, size):
     # the levels are not degenerate (the synthetic scales keep all three levels in use)
     assert len(np.unique(L_want)) == 3
     assert trunk.macs == sum(c.macs() for c in si.cfg3(batch)) if size == 56 else True
+
+
+def test_trunk_full_batch_sampled_images():
+    # the launch configuration bench.py times (batch 64); images are independent, so the oracle
+    # pipeline is run on the first and the last image only
+    blocks = si.trunk_params()
+    batch = 64
+    x = si.trunk_input(batch)
+    in_alpha = (0.6, 0.7)
+    trunk = rt.Trunk(to_gpu_blocks(blocks), batch, 56, in_alpha, device=DEV)
+    f_got, p_got = trunk.forward(dev(x))
+    f_got = f_got.cpu().numpy()
+    interior, _, _ = decode_bordered(p_got, batch, 7, 7, 512, 1)
+    for b in (0, batch - 1):
+        f_want, L_want = oracle_trunk(blocks, x[b:b + 1], in_alpha)
+        assert np.array_equal(f_got[b:b + 1], f_want)
+        assert np.array_equal(interior[b:b + 1], L_want)
+    assert trunk.macs == sum(c.macs() for c in si.cfg3(batch))
