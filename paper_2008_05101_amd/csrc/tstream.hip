@@ -68,7 +68,13 @@ template <int R, int CW, int ST, int U>
 struct StreamShape {
     static constexpr int PD = 2 * CW;                        // dwords per packed pixel
     static constexpr int SP = (U - 1) * ST + R;              // input pixels per image-row strip
-    static constexpr int PB = (16 / PD) > 0 ? (16 / PD) : 1; // pixels per batch (one 64-byte request where possible)
+    // pixels per batch: one 64-byte request where possible, except where a slightly different
+    // size makes the number of batches per group even (an odd number needs the group body twice,
+    // once per buffer parity, and the doubled code costs instruction-cache misses at kernel start)
+    static constexpr int PB = (R == 3 && CW == 4 && ST == 1 && U == 4)   ? 3
+                              : (R == 3 && CW == 2 && ST == 1 && U == 8) ? 5
+                              : (R == 3 && CW == 2 && ST == 2 && U == 4) ? 5
+                              : ((16 / PD) > 0 ? (16 / PD) : 1);
     static constexpr int CH = (SP + PB - 1) / PB;            // batches per strip
     static constexpr int NBATCH = R * CH;                    // batches per group
     static constexpr int BUF = PB * PD;                      // dwords per batch buffer
