@@ -232,7 +232,13 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
     const int64_t Hs = H + 2 * xb, Ws = W + 2 * xb;
     const int pad_s = pad - xb;
     const int64_t stored_bytes = (B * Hs * Ws + FATNN_BORDER_SLACK_PIXELS) * Cw * (int64_t)sizeof(plane2);
-    if (bordered && stored_bytes < 0xFFFFFFFFLL && want_stream(op, R, S, Cw, stride)) {
+    // the streaming kernel addresses its input, its outputs and the next layer's buffer with
+    // 32-bit byte offsets
+    const int64_t out_bytes = cs.N * Cout * 4;
+    const int64_t next_bytes =
+        chain != nullptr ? (int64_t)fatnn_bordered_act_bytes(B, cs.Ho, cs.Wo, Cout, chain->out_border) : 0;
+    if (bordered && stored_bytes < 0xFFFFFFFFLL && out_bytes < 0xFFFFFFFFLL && next_bytes < 0xFFFFFFFFLL &&
+        want_stream(op, R, S, Cw, stride)) {
         StreamParams q{};
         q.Wi = reinterpret_cast<const plane2*>(reinterpret_cast<const char*>(Wp) +
                                                fatnn_weight_interleaved_offset(Cout, cs.K));
@@ -248,9 +254,9 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
         q.K = (int32_t)cs.K;
         q.M = (int32_t)Cout;
         q.Kw = (int32_t)(cs.K / 32);
-        q.C = Y; q.Cf = Yf; q.ldc_n = Cout;
+        q.C = Y; q.Cf = Yf; q.ldc = (int32_t)Cout;
         q.scale = scale; q.bias = bias;
-        q.B = (int32_t)B; q.Hp = (int32_t)Hs; q.Wp = (int32_t)Ws; q.Ho = (int32_t)cs.Ho; q.Wo = (int32_t)cs.Wo;
+        q.Hp = (int32_t)Hs; q.Wp = (int32_t)Ws; q.Ho = (int32_t)cs.Ho;
         q.xoff = xb - pad;
         if (chain != nullptr) {
             q.Xn = reinterpret_cast<plane2*>(chain->Xnext);
@@ -263,8 +269,12 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
             q.relu = chain->relu;
         }
         const int U = stream_group_size(R, Cw, stride);
-        const int64_t ngroups = B * cs.Ho * ((cs.Wo + U - 1) / U);
+        q.wgroups = (int32_t)((cs.Wo + U - 1) / U);
+        q.tailU = (int32_t)(cs.Wo - (int64_t)(q.wgroups - 1) * U);
+        const int64_t ngroups = B * cs.Ho * q.wgroups;
         const int ranges = stream_ranges(Cout, ngroups, U, q.Kw, stream_max_groups_per_range(R, Cw, stride));
+        q.gq = (int32_t)(ngroups / ranges);
+        q.gr = (int32_t)(ngroups % ranges);
         return launch_stream_conv(q, op, R, Cw, stride, ranges, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
     }
     if (chain != nullptr) return FATNN_ERR_UNSUPPORTED;   // the chaining epilogue lives in the streaming kernel

@@ -10,6 +10,13 @@ namespace fatnn {
 
 constexpr int kWave = 64;
 
+// Places the next instruction at an address that is 4 modulo 8.  The hot loops are long runs
+// of 8-byte VOP3 instructions (v_bitop3_b32, v_bcnt_u32_b32); measured on gfx950, such a run
+// issues about 10 % faster when its instructions straddle the 8-byte boundaries than when
+// they sit on them (same instructions, same registers, only the code address differs), so
+// each run is started at the faster phase.  Costs one or two s_nop.
+#define FATNN_VOP3_RUN_PHASE() asm volatile(".p2align 3\n\ts_nop 0")
+
 // A packed element pair: two 32-bit plane words covering 32 consecutive k.
 using plane2 = uint2;
 
@@ -95,10 +102,12 @@ struct StreamParams {
     int32_t M, Kw;
     int32_t* C;
     float* Cf;
-    int64_t ldc_n;
+    int32_t ldc;            // elements between consecutive output pixels (= output channels)
     const float* scale;
     const float* bias;
-    int32_t B, Hp, Wp, Ho, Wo;
+    int32_t Hp, Wp, Ho;     // bordered input height / width, output height
+    int32_t wgroups, tailU; // groups of U output pixels per output row; pixels in the last one
+    int32_t gq, gr;         // groups per range of the grid: range r owns gq + (r < gr)
     int32_t xoff;           // physical border minus the convolution's padding (0 or 1)
     // Layer-chaining epilogue (Xn != nullptr): affine, optional skip and ReLU in fp32, then the
     // next layer's activation quantizer and packing straight into its bordered input buffer.

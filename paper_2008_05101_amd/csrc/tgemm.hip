@@ -131,12 +131,20 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
     __shared__ __attribute__((aligned(16))) plane2 As[2][KT][PA];
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
-    // tiles so that the tiles sharing an activation panel meet in one L2.
+    // logical tiles, and order the logical tiles in bands of kBand tile rows walked column by
+    // column, so that the ~64 tiles resident on one XCD at a time form a roughly square block
+    // (8 weight panels x 8 activation panels) and share their operand panels in that XCD's L2.
+    constexpr int kBand = 8;
     const int per_xcd = gridDim.x >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (logical >= ntiles) return;
-    const int tile_m = logical % tiles_m;
-    const int tile_n = logical / tiles_m;
+    const int tiles_n = ntiles / tiles_m;
+    const int band = logical / (kBand * tiles_n);
+    const int band_m0 = band * kBand;
+    const int band_rows = (tiles_m - band_m0) < kBand ? (tiles_m - band_m0) : kBand;
+    const int in_band = logical - band * kBand * tiles_n;
+    const int tile_m = band_m0 + in_band % band_rows;
+    const int tile_n = in_band / band_rows;
     const int row0 = tile_m * BM;
     const int col0 = tile_n * BN;
 
@@ -287,6 +295,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
             for (int j = 0; j < KT; ++j) {
                 if (j >= jn) break;
                 if (j + 1 < KT && j + 1 < jn) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+                FATNN_VOP3_RUN_PHASE();
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -83,7 +83,11 @@ struct StreamShape {
 // Columns whose partial sums a wavefront may keep in LDS between two passes over K.
 constexpr int kPassCols = 64;
 
-template <int OP, int R, int CW, int CWT, int ST, int U>
+// What happens to the finished sums: EPI_PLAIN writes int32 (and/or scaled fp32) NHWC outputs;
+// EPI_CHAIN applies the fused layer epilogue and writes the next layer's packed input.
+enum : int { EPI_PLAIN = 0, EPI_CHAIN = 1 };
+
+template <int OP, int R, int CW, int CWT, int ST, int U, int EPI>
 __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) {
     typedef StreamShape<R, CW, ST, U> Sh;
     constexpr int TAPS = R * R, PD = Sh::PD, SP = Sh::SP, PB = Sh::PB, CH = Sh::CH, NBATCH = Sh::NBATCH;
@@ -106,49 +110,62 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     float sc = 0.f, bs = 0.f;
     if (m_ok) {
         if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
-        if (p.Cf != nullptr || p.Xn != nullptr) {
+        if (EPI == EPI_CHAIN || p.Cf != nullptr) {
             sc = p.scale[m];
             if (p.bias != nullptr) bs = p.bias[m];
         }
     }
 
-    // ---- this wavefront's range of groups; a group = U neighbouring pixels of one output row ----
-    const int wgroups = (p.Wo + U - 1) / U;
-    const int64_t ngroups = (int64_t)p.B * p.Ho * wgroups;
-    const int nranges = gridDim.x;
+    // ---- this wavefront's range of groups; a group = U neighbouring pixels of one output row.
+    // Range r owns gq + (r < gr) groups: the ranges that get one group more are the first ones
+    // in dispatch order, which the hardware spreads over the compute units (a stride between
+    // them would put them all on the same SIMDs and make those finish a whole group late).
     const int range = blockIdx.x;
-    const int g_begin = (int)(((int64_t)range * ngroups) / nranges);
-    const int g_end = (int)(((int64_t)(range + 1) * ngroups) / nranges);
-    if (g_begin >= g_end) return;
+    const int g_begin = range * p.gq + (range < p.gr ? range : p.gr);
+    const int count = p.gq + (range < p.gr ? 1 : 0);
+    if (count == 0) return;
 
-    int wg, ho, b;
-    int32_t* const my_partials = pass_partials + (size_t)wave_in_block * kPassCols * 64 + lane;
-
-    sbytes_t xbase = (sbytes_t)(uintptr_t)p.A;
+    // All positions are 32-bit offsets that advance from group to group (the host checks that
+    // the input, the outputs and the next layer's buffer are each smaller than 4 GiB).
+    const int wgroups = p.wgroups;
     constexpr uint32_t kPixBytes = CWT * 8u;
-    const uint32_t row_bytes = (uint32_t)p.Wp * kPixBytes;     // bordered row; the tensor is < 4 GiB (host check)
+    constexpr uint32_t kInStep = (uint32_t)(U * ST) * kPixBytes;
+    const uint32_t row_bytes = (uint32_t)p.Wp * kPixBytes;
     const uint32_t img_bytes = (uint32_t)p.Hp * row_bytes;
+    const uint32_t in_row_adj = (uint32_t)ST * row_bytes - (uint32_t)(wgroups - 1) * kInStep;
+    const uint32_t in_img_adj = img_bytes - (uint32_t)((p.Ho - 1) * ST) * row_bytes - (uint32_t)(wgroups - 1) * kInStep;
+    const uint32_t ldc = (uint32_t)p.ldc;
+    const uint32_t out_step = (uint32_t)U * ldc, out_tail = (uint32_t)p.tailU * ldc;
+    const uint32_t nx_step = (uint32_t)(U * p.nCw);
+    const uint32_t nx_row_adj = (uint32_t)((p.nWp - (wgroups - 1) * U) * p.nCw);
+    const uint32_t nx_img_adj = (uint32_t)(((p.nHp - p.Ho + 1) * p.nWp - (wgroups - 1) * U) * p.nCw);
 
-    // byte offset of the first input pixel of the current group's first strip (bordered coordinates)
-    auto strip_offset = [&]() {
-        return (uint32_t)b * img_bytes + (uint32_t)(ho * ST + p.xoff) * row_bytes +
+    int wg, ho;                 // group in the output row, output row in the image
+    uint32_t goff;              // byte offset of the group's first strip in the bordered input
+    uint32_t ooff;              // element offset of the group's first output pixel, channel 0
+    uint32_t noff = 0;          // word-pair offset of that pixel in the next layer's bordered input
+    auto seek = [&]() {
+        wg = g_begin % wgroups;
+        const int t0 = g_begin / wgroups;
+        ho = t0 % p.Ho;
+        const int b = t0 / p.Ho;
+        goff = (uint32_t)b * img_bytes + (uint32_t)(ho * ST + p.xoff) * row_bytes +
                (uint32_t)(wg * U * ST + p.xoff) * kPixBytes;
+        const int Wo = (wgroups - 1) * U + p.tailU;
+        ooff = (uint32_t)((b * p.Ho + ho) * Wo + wg * U) * ldc;
+        if (EPI == EPI_CHAIN)
+            noff = (uint32_t)(((b * p.nHp + ho + p.nborder) * p.nWp + wg * U + p.nborder) * p.nCw);
     };
-    auto advance = [&]() {
-        if (++wg == wgroups) {
-            wg = 0;
-            if (++ho == p.Ho) {
-                ho = 0;
-                ++b;
-            }
-        }
-    };
+
+    int32_t* const my_partials = pass_partials + (size_t)wave_in_block * kPassCols * 64 + lane;
+    sbytes_t xbase = (sbytes_t)(uintptr_t)p.A;
+
     // batch i of a group = pixels [c*PB, c*PB+np) of the strip of filter row r
-    auto issue = [&](auto i_tag, uint32_t goff, uint32_t* dst) {
+    auto issue = [&](auto i_tag, uint32_t at, uint32_t* dst) {
         constexpr int i = decltype(i_tag)::value;
         constexpr int r = i / CH, c = i % CH;
         constexpr int np = (SP - c * PB) < PB ? (SP - c * PB) : PB;
-        const sptr_t src = (sptr_t)(xbase + (goff + (uint32_t)r * row_bytes + (uint32_t)(c * PB) * kPixBytes));
+        const sptr_t src = (sptr_t)(xbase + (at + (uint32_t)r * row_bytes + (uint32_t)(c * PB) * kPixBytes));
         sload_run<np * PD>(src, dst);
     };
 
@@ -186,24 +203,50 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     };
 
     uint32_t buf[2][Sh::BUF];
-    uint32_t goff = 0;
     int pass = 0;
+    const uint32_t lane_out = (uint32_t)m;   // this lane's channel inside an output pixel
 
     // One group: batch i+1 (or batch 0 of the next group) is in flight while batch i is
     // consumed.  A scalar-load wait waits for every outstanding load, so the wait for batch
     // i comes BEFORE batch i+1 is issued.  PAR = which buffer holds batch 0.
-    auto run_group = [&](auto par_tag, int g) {
+    auto run_group = [&](auto par_tag, int gi) {
         constexpr int PAR = decltype(par_tag)::value;
-        const int wo0 = wg * U;
-        const int64_t n0 = ((int64_t)b * p.Ho + ho) * p.Wo + wo0;
-        // first pixel of the group in the next layer's bordered input (chaining epilogue only)
-        const int64_t nx0 = ((int64_t)b * p.nHp + ho + p.nborder) * p.nWp + wo0 + p.nborder;
+        const uint32_t o0 = ooff, n0 = noff;
+        const int nu = (wg == wgroups - 1) ? p.tailU : U;   // output pixels of this group that exist
         uint32_t goff_next = goff;
-        if (g + 1 < g_end) {
-            advance();
-            goff_next = strip_offset();
+        if (gi + 1 < count) {
+            if (wg + 1 < wgroups) {
+                ++wg;
+                goff_next = goff + kInStep;
+                ooff += out_step;
+                if (EPI == EPI_CHAIN) noff += nx_step;
+            } else {
+                wg = 0;
+                ooff += out_tail;
+                if (ho + 1 < p.Ho) {
+                    ++ho;
+                    goff_next = goff + in_row_adj;
+                    if (EPI == EPI_CHAIN) noff += nx_row_adj;
+                } else {
+                    ho = 0;
+                    goff_next = goff + in_img_adj;
+                    if (EPI == EPI_CHAIN) noff += nx_img_adj;
+                }
+            }
         }
-        const int col_local = (g - g_begin) * U;
+        const int col_local = gi * U;
+        const bool last_pass = NPASS == 1 || pass + 1 == NPASS;
+        // the skip values of the group are requested now and used after the K loop
+        float sk[U];
+        if constexpr (EPI == EPI_CHAIN) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                sk[u] = 0.0f;
+                if (last_pass && p.skip != nullptr && u < nu && m_ok)
+                    sk[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.skip) +
+                                                            (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u));
+            }
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             acc[u] = 0;
@@ -224,49 +267,53 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         [&]<int... I>(std::integer_sequence<int, I...>) { (step(std::integral_constant<int, I>{}), ...); }
         (std::make_integer_sequence<int, NBATCH>{});
         goff = goff_next;
-        if (NPASS > 1 && pass + 1 < NPASS) {
+        if (!last_pass) {
 #pragma unroll
             for (int u = 0; u < U; ++u) my_partials[(col_local + u) * 64] = acc[u];
             return;
         }
-        if (p.Xn != nullptr) {
+        if constexpr (EPI == EPI_CHAIN) {
             // Layer chaining (Supplementary S1: batch norm folded into the layer, ReLU and the skip
             // connection fused, packing fused): the 64 channels of a wavefront are 64 lanes, so a
             // wave-wide ballot of the two quantizer comparisons IS the pair of plane words.
+            const uint32_t cw = (uint32_t)(2 * mb + lane);   // lanes 0 and 1 write one word pair each
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (wo0 + u >= p.Wo) break;
+                if (u >= nu) break;
                 const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : (OP == OP_XOR_PAIR ? p.K - p.cmul * acc[u] : p.K - (acc[u] >> 1));
                 float f = sc * (float)v;
                 if (p.bias != nullptr) f = f + bs;
-                const int64_t o = (n0 + u) * p.ldc_n + m;
-                if (p.skip != nullptr && m_ok) f = f + p.skip[o];
+                if (p.skip != nullptr) f = f + sk[u];
                 if (p.relu) f = fmaxf(f, 0.0f);
-                if (p.Cf != nullptr && m_ok) __builtin_nontemporal_store(f, &p.Cf[o]);
+                if (p.Cf != nullptr && m_ok)
+                    __builtin_nontemporal_store(f, reinterpret_cast<float*>(reinterpret_cast<char*>(p.Cf) +
+                                                                            (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u)));
                 const bool nan = f != f;
                 const uint64_t lo = __ballot(m_ok && ((f >= p.t1) || (nan && p.nan_lo != 0u)));
                 const uint64_t hi = __ballot(m_ok && (f >= p.t2));
-                const int cw = 2 * mb + lane;            // lanes 0 and 1 write one word pair each
-                if (lane < 2 && cw < p.nCw) {
+                if (lane < 2 && cw < (uint32_t)p.nCw) {
                     plane2 word;
                     word.x = (uint32_t)(lane == 0 ? hi : hi >> 32);
                     word.y = (uint32_t)(lane == 0 ? lo : lo >> 32);
-                    p.Xn[(nx0 + u) * p.nCw + cw] = word;
+                    *reinterpret_cast<plane2*>(reinterpret_cast<char*>(p.Xn) +
+                                               (size_t)((n0 + (uint32_t)(u * p.nCw) + cw) * 8u)) = word;
                 }
             }
-            return;
-        }
+        } else {
+            if (m_ok) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (wo0 + u < p.Wo && m_ok) {
-                const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : (OP == OP_XOR_PAIR ? p.K - p.cmul * acc[u] : p.K - (acc[u] >> 1));
-                const int64_t o = (n0 + u) * p.ldc_n + m;
-                // outputs are written once and not read again by this kernel: stream them out
-                if (p.C != nullptr) __builtin_nontemporal_store(v, &p.C[o]);
-                if (p.Cf != nullptr) {
-                    float f = sc * (float)v;
-                    if (p.bias != nullptr) f = f + bs;
-                    __builtin_nontemporal_store(f, &p.Cf[o]);
+                for (int u = 0; u < U; ++u) {
+                    if (u >= nu) break;
+                    const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : (OP == OP_XOR_PAIR ? p.K - p.cmul * acc[u] : p.K - (acc[u] >> 1));
+                    const size_t ob = (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u);
+                    // outputs are written once and not read again by this kernel: stream them out
+                    if (p.C != nullptr)
+                        __builtin_nontemporal_store(v, reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.C) + ob));
+                    if (p.Cf != nullptr) {
+                        float f = sc * (float)v;
+                        if (p.bias != nullptr) f = f + bs;
+                        __builtin_nontemporal_store(f, reinterpret_cast<float*>(reinterpret_cast<char*>(p.Cf) + ob));
+                    }
                 }
             }
         }
@@ -279,22 +326,18 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
 #pragma unroll
             for (int c = 0; c < CW; ++c) w[t][c] = wsrc[(int64_t)(t * CWT + pass * CW + c) * 64];
         xbase = (sbytes_t)(uintptr_t)p.A + (uint32_t)pass * (CW * 8u);
-        wg = g_begin % wgroups;
-        const int t0 = g_begin / wgroups;
-        ho = t0 % p.Ho;
-        b = t0 / p.Ho;
-        goff = strip_offset();
+        seek();
         issue(std::integral_constant<int, 0>{}, goff, buf[0]);
 
-        int g = g_begin;
-        while (g < g_end) {
-            run_group(std::integral_constant<int, 0>{}, g);
-            ++g;
+        int gi = 0;
+        while (gi < count) {
+            run_group(std::integral_constant<int, 0>{}, gi);
+            ++gi;
             if constexpr ((NBATCH & 1) != 0) {
                 // an odd number of batches leaves the prefetched batch in the other buffer
-                if (g < g_end) {
-                    run_group(std::integral_constant<int, 1>{}, g);
-                    ++g;
+                if (gi < count) {
+                    run_group(std::integral_constant<int, 1>{}, gi);
+                    ++gi;
                 } else {
                     break;
                 }
@@ -310,8 +353,16 @@ int launch_inst(const StreamParams& p, int ranges, hipStream_t stream) {
     dim3 grid((unsigned)ranges, (unsigned)((mblocks + wpb - 1) / wpb));
     const size_t lds = (CWT > CW) ? (size_t)wpb * kPassCols * 64 * sizeof(int32_t) : 0;
     const LaunchTiming t = take_launch_timing();
-    hipExtLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U>), grid, dim3(64 * wpb), lds, stream, t.start,
-                          t.stop, 0, p);
+    if (p.Xn != nullptr) {
+        if constexpr (OP == OP_TERNARY)
+            hipExtLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_CHAIN>), grid, dim3(64 * wpb), lds,
+                                  stream, t.start, t.stop, 0, p);
+        else
+            return -3;
+    } else {
+        hipExtLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_PLAIN>), grid, dim3(64 * wpb), lds, stream,
+                              t.start, t.stop, 0, p);
+    }
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
