@@ -35,6 +35,12 @@ __device__ __forceinline__ void popc_acc(int32_t& acc, uint32_t x) {
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
 }
 
+// v[LANE] = s for a wave-uniform s; the other lanes keep their value.
+template <int LANE>
+__device__ __forceinline__ void write_lane(uint32_t& v, uint32_t s) {
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(LANE));
+}
+
 // Wave-uniform load of NW consecutive dwords through the scalar cache (dword alignment suffices).
 template <int NW>
 __device__ __forceinline__ void sload(const sptr_t src, uint32_t* dst) {
@@ -101,19 +107,24 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     // blockIdx.y = group of row blocks, wave = row block inside the group; blockIdx.x = range of groups
     const int mb = blockIdx.y * (blockDim.x >> 6) + wave_in_block;
     if (mb * 64 >= p.M) return;
-    const int m = mb * 64 + lane;
-    const bool m_ok = m < p.M;
+    // Lanes past the last output channel (M not a multiple of 64) take the last channel's
+    // constants and output slot: they compute and store a duplicate of that channel, which
+    // saves every per-lane mask in the epilogues; only the quantizer ballots drop their bits.
+    const int m_real = mb * 64 + lane;
+    const bool m_ok = m_real < p.M;
+    const int m = m_ok ? m_real : p.M - 1;
+    const uint64_t ok_mask = __ballot(m_ok);
 
     plane2 w[TAPS][CW];   // weights of this lane's output channel for the current pass
-    const plane2* wsrc = p.Wi + ((int64_t)mb * p.Kw) * 64 + lane;
+    const plane2* wsrc = p.Wi + ((int64_t)mb * p.Kw) * 64 + (m - mb * 64);   // duplicates read the last channel's weights
     int32_t rc = 0;
-    float sc = 0.f, bs = 0.f;
-    if (m_ok) {
-        if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
-        if (EPI == EPI_CHAIN || p.Cf != nullptr) {
-            sc = p.scale[m];
-            if (p.bias != nullptr) bs = p.bias[m];
-        }
+    // a missing bias (and a missing skip value below) is -0.0f: x + (-0.0f) == x bit for bit for
+    // every x, so the additions need no condition
+    float sc = 0.f, bs = -0.0f;
+    if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
+    if (EPI == EPI_CHAIN || p.Cf != nullptr) {
+        sc = p.scale[m];
+        if (p.bias != nullptr) bs = p.bias[m];
     }
 
     // ---- this wavefront's range of groups; a group = U neighbouring pixels of one output row.
@@ -205,6 +216,11 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     uint32_t buf[2][Sh::BUF];
     int pass = 0;
     const uint32_t lane_out = (uint32_t)m;   // this lane's channel inside an output pixel
+    // Chaining epilogue: lane 2u+h stores half h (channels 32h..32h+31 of this wavefront's 64)
+    // of output pixel u as one word pair of the next layer's input.
+    const uint32_t xn_word = (uint32_t)(2 * mb + (lane & 1));
+    const bool xn_lane_ok = lane < 2 * U && xn_word < (uint32_t)p.nCw;
+    const uint32_t xn_lane_off = ((uint32_t)(lane >> 1) * (uint32_t)p.nCw + xn_word) * 8u;
 
     // One group: batch i+1 (or batch 0 of the next group) is in flight while batch i is
     // consumed.  A scalar-load wait waits for every outstanding load, so the wait for batch
@@ -241,8 +257,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         if constexpr (EPI == EPI_CHAIN) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                sk[u] = 0.0f;
-                if (last_pass && p.skip != nullptr && u < nu && m_ok)
+                sk[u] = -0.0f;
+                if (last_pass && p.skip != nullptr && u < nu)
                     sk[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.skip) +
                                                             (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u));
             }
@@ -276,31 +292,40 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
             // Layer chaining (Supplementary S1: batch norm folded into the layer, ReLU and the skip
             // connection fused, packing fused): the 64 channels of a wavefront are 64 lanes, so a
             // wave-wide ballot of the two quantizer comparisons IS the pair of plane words.
-            const uint32_t cw = (uint32_t)(2 * mb + lane);   // lanes 0 and 1 write one word pair each
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (u >= nu) break;
+            uint32_t wx = 0, wy = 0;
+            auto pixel = [&](auto u_tag) {
+                constexpr int u = decltype(u_tag)::value;
                 const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : (OP == OP_XOR_PAIR ? p.K - p.cmul * acc[u] : p.K - (acc[u] >> 1));
                 float f = sc * (float)v;
-                if (p.bias != nullptr) f = f + bs;
-                if (p.skip != nullptr) f = f + sk[u];
-                if (p.relu) f = fmaxf(f, 0.0f);
-                if (p.Cf != nullptr && m_ok)
+                f = f + bs;
+                f = f + sk[u];
+                if (p.relu) {
+                    f = fmaxf(f, 0.0f);
+                    asm volatile("" : "+v"(f));   // keeps this a scalar branch instead of a per-lane select
+                }
+                if (p.Cf != nullptr)
                     __builtin_nontemporal_store(f, reinterpret_cast<float*>(reinterpret_cast<char*>(p.Cf) +
                                                                             (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u)));
                 const bool nan = f != f;
-                const uint64_t lo = __ballot(m_ok && ((f >= p.t1) || (nan && p.nan_lo != 0u)));
-                const uint64_t hi = __ballot(m_ok && (f >= p.t2));
-                if (lane < 2 && cw < (uint32_t)p.nCw) {
-                    plane2 word;
-                    word.x = (uint32_t)(lane == 0 ? hi : hi >> 32);
-                    word.y = (uint32_t)(lane == 0 ? lo : lo >> 32);
-                    *reinterpret_cast<plane2*>(reinterpret_cast<char*>(p.Xn) +
-                                               (size_t)((n0 + (uint32_t)(u * p.nCw) + cw) * 8u)) = word;
-                }
+                const uint64_t lo = __ballot((f >= p.t1) || (nan && p.nan_lo != 0u)) & ok_mask;
+                const uint64_t hi = __ballot(f >= p.t2) & ok_mask;
+                // lane 2u <- low halves, lane 2u+1 <- high halves of this pixel's ballots
+                write_lane<2 * u>(wx, (uint32_t)hi);
+                write_lane<2 * u + 1>(wx, (uint32_t)(hi >> 32));
+                write_lane<2 * u>(wy, (uint32_t)lo);
+                write_lane<2 * u + 1>(wy, (uint32_t)(lo >> 32));
+            };
+            [&]<int... UU>(std::integer_sequence<int, UU...>) {
+                ((UU < nu ? (pixel(std::integral_constant<int, UU>{}), 0) : 0), ...);
+            }(std::make_integer_sequence<int, U>{});
+            if (xn_lane_ok && lane < 2 * nu) {
+                plane2 word;
+                word.x = wx;
+                word.y = wy;
+                *reinterpret_cast<plane2*>(reinterpret_cast<char*>(p.Xn) + (size_t)(n0 * 8u + xn_lane_off)) = word;
             }
         } else {
-            if (m_ok) {
+            {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (u >= nu) break;
@@ -311,7 +336,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
                         __builtin_nontemporal_store(v, reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.C) + ob));
                     if (p.Cf != nullptr) {
                         float f = sc * (float)v;
-                        if (p.bias != nullptr) f = f + bs;
+                        f = f + bs;
                         __builtin_nontemporal_store(f, reinterpret_cast<float*>(reinterpret_cast<char*>(p.Cf) + ob));
                     }
                 }
