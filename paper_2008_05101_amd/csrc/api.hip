@@ -174,40 +174,12 @@ void set_ternary_consts(GemmParams& p, const void* Wp, int64_t M, int64_t K, int
 }
 
 // Which convolution kernel serves a call.  FATNN_CONV_KERNEL=tiled overrides the
-// choice (for measurements); FATNN_STREAM_WPS sets the wavefronts per SIMD of the
-// streaming kernel.
+// choice (for measurements).
 bool want_stream(int op, int R, int S, int Cw, int stride) {
     if (!stream_supported(op, R, S, Cw, stride)) return false;
     const char* e = getenv("FATNN_CONV_KERNEL");
     if (e != nullptr && e[0] == 't') return false;
     return true;
-}
-
-// Number of ranges of pixel groups (= wavefronts per block of 64 output channels).  All
-// wavefronts are meant to be resident at once, the same number on every SIMD, and
-// each should see enough groups to amortise loading its weights.
-int stream_ranges(int64_t M, int64_t ngroups, int64_t group_size, int64_t Kw, int64_t max_groups_per_range) {
-    const int64_t mblocks = (M + 63) / 64;
-    const int64_t vgprs = 2 * (Kw > 72 ? 72 : Kw) + 24;
-    int64_t occ = 512 / vgprs;
-    if (occ > 8) occ = 8;
-    if (occ < 1) occ = 1;
-    // as many wavefronts per SIMD as the registers allow (up to 6: more only adds weight-load
-    // traffic at the start), but at least three pixel groups per wavefront
-    int64_t wps = occ < 6 ? occ : 6;
-    while (wps > 1 && ngroups * mblocks < 3 * 1024 * wps) --wps;
-    (void)group_size;
-    const char* e = getenv("FATNN_STREAM_WPS");
-    if (e != nullptr && atoi(e) > 0) {
-        wps = atoi(e);
-        if (wps > occ) wps = occ;
-    }
-    int64_t ranges = (1024 * wps) / mblocks;
-    if (ranges < 1) ranges = 1;
-    const int64_t need = (ngroups + max_groups_per_range - 1) / max_groups_per_range;
-    if (ranges < need) ranges = need;
-    if (ranges > ngroups) ranges = ngroups;
-    return (int)ranges;
 }
 
 struct ChainArgs {
@@ -268,14 +240,7 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
             q.t1 = chain->t1; q.t2 = chain->t2; q.nan_lo = chain->nan_lo;
             q.relu = chain->relu;
         }
-        const int U = stream_group_size(R, Cw, stride);
-        q.wgroups = (int32_t)((cs.Wo + U - 1) / U);
-        q.tailU = (int32_t)(cs.Wo - (int64_t)(q.wgroups - 1) * U);
-        const int64_t ngroups = B * cs.Ho * q.wgroups;
-        const int ranges = stream_ranges(Cout, ngroups, U, q.Kw, stream_max_groups_per_range(R, Cw, stride));
-        q.gq = (int32_t)(ngroups / ranges);
-        q.gr = (int32_t)(ngroups % ranges);
-        return launch_stream_conv(q, op, R, Cw, stride, ranges, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+        return launch_stream_conv(q, op, R, Cw, stride, B * cs.Ho, cs.Wo, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
     }
     if (chain != nullptr) return FATNN_ERR_UNSUPPORTED;   // the chaining epilogue lives in the streaming kernel
     GemmParams p{};

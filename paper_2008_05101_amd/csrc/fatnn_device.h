@@ -120,9 +120,9 @@ struct StreamParams {
 };
 
 bool stream_supported(int op, int R, int S, int Cw, int stride);
-int stream_group_size(int R, int Cw, int stride);
-int stream_max_groups_per_range(int R, int Cw, int stride);
-int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int ranges, hipStream_t stream);
+// out_rows = batch x output height, Wo = output width; wgroups, tailU, gq and gr are filled in here.
+int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo,
+                       hipStream_t stream);
 
 // Bordered activation packing: levels NHWC [B][H][W][C] -> [B][H+2*border][W+2*border][C/32]
 // word pairs, ring pixels = border_word; `slack_pixels` more pixels of border_word follow.

@@ -104,8 +104,13 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     extern __shared__ int32_t pass_partials[];
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // blockIdx.y = group of row blocks, wave = row block inside the group; blockIdx.x = range of groups
-    const int mb = blockIdx.y * (blockDim.x >> 6) + wave_in_block;
+    // One-dimensional grid: workgroup = (range of groups, set of row blocks), the row-block set
+    // varying fastest, so that in dispatch order the ranges come one after the other; wave = row
+    // block inside the set.
+    const int wpb = blockDim.x >> 6;
+    const int nsets = ((p.M + 63) / 64 + wpb - 1) / wpb;
+    const int range = blockIdx.x / nsets;
+    const int mb = (blockIdx.x - range * nsets) * wpb + wave_in_block;
     if (mb * 64 >= p.M) return;
     // Lanes past the last output channel (M not a multiple of 64) take the last channel's
     // constants and output slot: they compute and store a duplicate of that channel, which
@@ -131,7 +136,6 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     // Range r owns gq + (r < gr) groups: the ranges that get one group more are the first ones
     // in dispatch order, which the hardware spreads over the compute units (a stride between
     // them would put them all on the same SIMDs and make those finish a whole group late).
-    const int range = blockIdx.x;
     const int g_begin = range * p.gq + (range < p.gr ? range : p.gr);
     const int count = p.gq + (range < p.gr ? 1 : 0);
     if (count == 0) return;
@@ -252,16 +256,22 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         }
         const int col_local = gi * U;
         const bool last_pass = NPASS == 1 || pass + 1 == NPASS;
-        // the skip values of the group are requested now and used after the K loop
+        // The skip values of the group are requested now and used after the K loop, where the
+        // registers allow it; with eight resident channel words and seven accumulators they are
+        // requested in the epilogue.
+        constexpr bool kSkipEarly = !(CW >= 8 && U >= 7);
         float sk[U];
-        if constexpr (EPI == EPI_CHAIN) {
+        auto load_skips = [&]() {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 sk[u] = -0.0f;
-                if (last_pass && p.skip != nullptr && u < nu)
+                if (p.skip != nullptr && u < nu)
                     sk[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.skip) +
                                                             (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u));
             }
+        };
+        if constexpr (EPI == EPI_CHAIN && kSkipEarly) {
+            if (last_pass) load_skips();
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -292,6 +302,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
             // Layer chaining (Supplementary S1: batch norm folded into the layer, ReLU and the skip
             // connection fused, packing fused): the 64 channels of a wavefront are 64 lanes, so a
             // wave-wide ballot of the two quantizer comparisons IS the pair of plane words.
+            if constexpr (!kSkipEarly) load_skips();
             uint32_t wx = 0, wy = 0;
             auto pixel = [&](auto u_tag) {
                 constexpr int u = decltype(u_tag)::value;
@@ -371,24 +382,71 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     }
 }
 
+// Wavefronts per SIMD that stay resident for a kernel at a workgroup size (asked once per
+// instantiation and workgroup size; the answer depends on the register count the compiler reached).
+template <typename Kernel>
+int resident_waves_per_simd(Kernel kernel, int wpb, size_t lds, int* cache) {
+    if (cache[wpb] == 0) {
+        int nblk = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, kernel, 64 * wpb, lds) != hipSuccess || nblk < 1) nblk = 1;
+        const int waves = nblk * wpb / 4;
+        cache[wpb] = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
+    }
+    return cache[wpb];
+}
+
+// Number of ranges of pixel groups (= wavefronts per block of 64 output channels).  All
+// wavefronts are meant to be resident at once, the same number on every SIMD, and each
+// should see enough groups to amortise loading its weights.  FATNN_STREAM_WPS sets the
+// wavefronts per SIMD (for measurements).
+int plan_ranges(int64_t mblocks, int64_t ngroups, int occ, int64_t max_groups_per_range) {
+    // as many wavefronts per SIMD as stay resident (up to 6: more only adds weight-load traffic
+    // at the start), but at least three pixel groups per wavefront
+    int64_t wps = occ < 6 ? occ : 6;
+    while (wps > 1 && ngroups * mblocks < 3 * 1024 * wps) --wps;
+    const char* e = getenv("FATNN_STREAM_WPS");
+    if (e != nullptr && atoi(e) > 0) {
+        wps = atoi(e);
+        if (wps > occ) wps = occ;
+    }
+    int64_t ranges = (1024 * wps) / mblocks;
+    if (ranges < 1) ranges = 1;
+    const int64_t need = (ngroups + max_groups_per_range - 1) / max_groups_per_range;
+    if (ranges < need) ranges = need;
+    if (ranges > ngroups) ranges = ngroups;
+    return (int)ranges;
+}
+
 template <int OP, int R, int CW, int CWT, int ST, int U>
-int launch_inst(const StreamParams& p, int ranges, hipStream_t stream) {
+int launch_inst(StreamParams p, int64_t out_rows, int64_t Wo, hipStream_t stream) {
+    p.wgroups = (int32_t)((Wo + U - 1) / U);
+    p.tailU = (int32_t)(Wo - (int64_t)(p.wgroups - 1) * U);
+    const int64_t ngroups = out_rows * p.wgroups;
+    if (ngroups <= 0 || ngroups > 0x7FFFFFF0LL) return -2;
     const int mblocks = (p.M + 63) / 64;
     const int wpb = mblocks < 4 ? mblocks : 4;
-    dim3 grid((unsigned)ranges, (unsigned)((mblocks + wpb - 1) / wpb));
     const size_t lds = (CWT > CW) ? (size_t)wpb * kPassCols * 64 * sizeof(int32_t) : 0;
-    const LaunchTiming t = take_launch_timing();
+    const int64_t max_groups = (CWT > CW) ? kPassCols / U : 0x7FFFFFFF;
+    auto launch = [&](auto kernel, int* cache) {
+        const int occ = resident_waves_per_simd(kernel, wpb, lds, cache);
+        const int ranges = plan_ranges(mblocks, ngroups, occ, max_groups);
+        p.gq = (int32_t)(ngroups / ranges);
+        p.gr = (int32_t)(ngroups % ranges);
+        dim3 grid((unsigned)(ranges * ((mblocks + wpb - 1) / wpb)));
+        const LaunchTiming t = take_launch_timing();
+        hipExtLaunchKernelGGL(kernel, grid, dim3(64 * wpb), lds, stream, t.start, t.stop, 0, p);
+        return hipGetLastError() == hipSuccess ? 0 : -1;
+    };
     if (p.Xn != nullptr) {
-        if constexpr (OP == OP_TERNARY)
-            hipExtLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_CHAIN>), grid, dim3(64 * wpb), lds,
-                                  stream, t.start, t.stop, 0, p);
-        else
+        if constexpr (OP == OP_TERNARY) {
+            static int cache[5] = {0, 0, 0, 0, 0};
+            return launch(stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_CHAIN>, cache);
+        } else {
             return -3;
-    } else {
-        hipExtLaunchKernelGGL((stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_PLAIN>), grid, dim3(64 * wpb), lds, stream,
-                              t.start, t.stop, 0, p);
+        }
     }
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    static int cache[5] = {0, 0, 0, 0, 0};
+    return launch(stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_PLAIN>, cache);
 }
 
 // Output pixels per group for a filter size / channel-word count / stride.
@@ -399,15 +457,21 @@ constexpr int group_u(int R, int CW, int ST) {
 // Channel words kept in registers per pass: everything, except for 3x3 filters over 512 channels.
 constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : CWT; }
 
-}  // namespace
+// Shapes that also have a kernel with groups of seven output pixels: ResNet's 14- and 7-pixel
+// rows split into groups of 4 (or 2) leave the last group of every row partly empty.
+constexpr bool has_u7(int R, int CW, int ST) { return R == 3 && ST == 1 && (CW == 8 || CW == 16); }
 
-int stream_group_size(int R, int Cw, int stride) { return group_u(R, Cw, stride); }
-
-// Largest number of pixel groups one wavefront may own (bounded only for multi-pass shapes).
-int stream_max_groups_per_range(int R, int Cw, int stride) {
-    if (resident_cw(R, Cw) == Cw) return 0x7FFFFFFF;
-    return kPassCols / group_u(R, Cw, stride);
+// Output pixels per group for this call.  FATNN_STREAM_U7=0 switches the groups of seven off.
+int pick_group_size(int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo, int64_t mblocks) {
+    // groups of seven only where they still give every SIMD two wavefronts of three groups each
+    if (op == OP_TERNARY && has_u7(R, Cw, stride) && Wo % 7 == 0 && out_rows * (Wo / 7) * mblocks >= 6 * 1024) {
+        const char* e = getenv("FATNN_STREAM_U7");
+        if (e == nullptr || e[0] != '0') return 7;
+    }
+    return group_u(R, Cw, stride);
 }
+
+}  // namespace
 
 bool stream_supported(int op, int R, int S, int Cw, int stride) {
     if (op != OP_TERNARY && op != OP_TWOBIT_TERNARY && op != OP_XOR_PAIR) return false;
@@ -417,14 +481,19 @@ bool stream_supported(int op, int R, int S, int Cw, int stride) {
     return false;
 }
 
-int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int ranges, hipStream_t stream) {
+int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo,
+                       hipStream_t stream) {
+    const int U = pick_group_size(op, R, Cw, stride, out_rows, Wo, (p.M + 63) / 64);
 #define FATNN_STREAM_CASE(RR, CC, SS)                                                                          \
     if (R == RR && Cw == CC && stride == SS) {                                                                 \
         constexpr int UU = group_u(RR, CC, SS);                                                                \
         constexpr int RC = resident_cw(RR, CC);                                                                \
-        if (op == OP_TERNARY) return launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream);          \
-        if (op == OP_XOR_PAIR) return launch_inst<OP_XOR_PAIR, RR, RC, CC, SS, UU>(p, ranges, stream);        \
-        return launch_inst<OP_TWOBIT_TERNARY, RR, RC, CC, SS, UU>(p, ranges, stream);                          \
+        if constexpr (has_u7(RR, CC, SS)) {                                                                    \
+            if (U == 7) return launch_inst<OP_TERNARY, RR, RC, CC, SS, 7>(p, out_rows, Wo, stream);            \
+        }                                                                                                      \
+        if (op == OP_TERNARY) return launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);    \
+        if (op == OP_XOR_PAIR) return launch_inst<OP_XOR_PAIR, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);  \
+        return launch_inst<OP_TWOBIT_TERNARY, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);                    \
     }
     FATNN_STREAM_CASE(3, 2, 1)
     FATNN_STREAM_CASE(3, 4, 1)
