@@ -43,7 +43,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg3", "cfg5", "quantpack"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg3", "cfg5", "quantpack", "paper6"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -190,6 +190,63 @@ def side_workload(args, torch, fatnn, si, dev):
         }
         print(json.dumps(line))
         return
+    if args.workload == "paper6":
+        # The paper's layer-wise comparison (Section 5.1.1, Tables 4 / S2): six 3x3 layers, ternary vs the
+        # conventional two-bit form vs the xnor rule alone, at the paper's batch 1 and at batch 32.
+        code = torch.tensor([0, 1, 3], dtype=torch.int8, device=dev)
+        results = {}
+        tot_ms = 0.0
+        tot_ops = 0.0
+        best = None
+        for batch in (1, 32):
+            for case in si.paper_six(batch):
+                Lw, Lx = case.make()
+                Lw_d = torch.from_numpy(Lw).to(dev)
+                Lx_d = torch.from_numpy(Lx).to(dev)
+                Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT, fatnn.OHWI)
+                Xp = fatnn.pack_ternary_bordered(Lx_d, case.pad, case.act_mode)
+                W2 = fatnn.pack_twobit(code[Lw_d.long()], fatnn.WEIGHT, fatnn.OHWI)
+                X2 = fatnn.pack_twobit_bordered(code[Lx_d.long()], case.pad)
+                Y = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.int32, device=dev)
+                a = (case.B, case.Cin, case.H, case.W, case.Cout, case.R, case.S, case.stride, case.pad)
+                n, w = args.steps, args.warmup
+                t_ter = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *a, case.act_mode, out=Y,
+                                                                           x_layout=fatnn.X_BORDERED), n, w)
+                t_two = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *a, out=Y,
+                                                                          x_layout=fatnn.X_BORDERED), n, w)
+                t_xn = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *a, fatnn.BASIS_XNOR_ONLY, out=Y,
+                                                                         x_layout=fatnn.X_BORDERED), n, w)
+                ops = 2.0 * case.macs()
+                results[f"{case.name}_b{batch}"] = {
+                    "ternary_us": round(t_ter * 1e3, 2), "twobit_us": round(t_two * 1e3, 2),
+                    "xnor_only_us": round(t_xn * 1e3, 2), "ternary_tops": round(ops / (t_ter * 1e-3) / 1e12, 2),
+                    "speedup_vs_twobit": round(t_two / t_ter, 3), "extra_bit_ops_cost": round((t_ter - t_xn) / t_xn, 4)}
+                if batch == 32:
+                    tot_ms += t_ter
+                    tot_ops += ops
+                    if best is None or ops / t_ter > best[0]:
+                        best = (ops / t_ter, case.name, t_ter)
+                del Wp, Xp, W2, X2, Y, Lw_d, Lx_d
+        achieved = best[0] / 1e9
+        line = {
+            "metric": "ternary GEMM Tops/s (2MNK) at 1 MI355X", "value": round(tot_ops / (tot_ms * 1e-3) / 1e12, 3),
+            "unit": "Tops/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(tot_ms, 5),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+            "config": {"workload": "paper6: the six 3x3 layer shapes of the paper's layer-wise timing (64 channels at "
+                                   "28/56/112/224, 128 and 256 channels at 56), ternary vs two-bit vs xnor-only "
+                                   "kernels; value and ms_per_step are the six ternary layers at batch 32, inputs "
+                                   "already packed"},
+            "roofline": {"bound": "alu", "kernel": f"stream_conv_kernel on {best[1]} (batch 32)",
+                         "achieved": round(achieved, 2), "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s",
+                         "frac": round(achieved / TERNARY_PEAK_TOPS, 4), "traffic": None, "kernel_ms": round(best[2], 5)},
+            "cpu_baseline": None,
+            "extra": {"layers": results,
+                      "paper_context_us_nvidia_2080ti_batch1": {"ternary": [11, 14.5, 26, 90, 34, 87],
+                                                                "twobit": [38, 44, 73.5, 274, 91, 217.5]}},
+        }
+        print(json.dumps(line))
+        return
     if args.workload == "cfg5":
         # ragged and low-K shapes, packing of the activations included in every step
         results = {}
@@ -320,7 +377,7 @@ def main():
         return
 
     extra = {}
-    if args.workload in ("cfg3", "cfg5", "quantpack"):
+    if args.workload in ("cfg3", "cfg5", "quantpack", "paper6"):
         side_workload(args, torch, fatnn, si, dev)
         return
     if args.workload == "cfg2":

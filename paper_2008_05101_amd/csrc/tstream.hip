@@ -122,11 +122,14 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
 
     plane2 w[TAPS][CW];   // weights of this lane's output channel for the current pass
     const plane2* wsrc = p.Wi + ((int64_t)mb * p.Kw) * 64 + (m - mb * 64);   // duplicates read the last channel's weights
-    int32_t rc = 0;
+    // The row constant is loaded here but multiplied only in the epilogue: arithmetic on it in
+    // the prologue would make every wavefront wait out a memory round trip before it even
+    // requests its weights.
+    int32_t rc_raw = 0;
     // a missing bias (and a missing skip value below) is -0.0f: x + (-0.0f) == x bit for bit for
     // every x, so the additions need no condition
     float sc = 0.f, bs = -0.0f;
-    if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
+    if (OP == OP_TERNARY) rc_raw = p.rowc[m];
     if (EPI == EPI_CHAIN || p.Cf != nullptr) {
         sc = p.scale[m];
         if (p.bias != nullptr) bs = p.bias[m];
@@ -298,6 +301,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
             for (int u = 0; u < U; ++u) my_partials[(col_local + u) * 64] = acc[u];
             return;
         }
+        asm volatile("" : "+v"(rc_raw));   // keeps the multiply below out of the prologue
+        const int32_t rc = p.cmul * rc_raw;
         if constexpr (EPI == EPI_CHAIN) {
             // Layer chaining (Supplementary S1: batch norm folded into the layer, ReLU and the skip
             // connection fused, packing fused): the 64 channels of a wavefront are 64 lanes, so a

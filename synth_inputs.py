@@ -187,6 +187,14 @@ def cfg5_bottleneck(batch: int = 128) -> List[ConvCase]:
     ]
 
 
+def paper_six(batch: int = 1) -> List[ConvCase]:
+    """The six layer shapes of the paper's layer-wise timing (Section 5.1.1): 3x3, stride 1, pad 1, equal
+    input and output channels; 64 channels at 28, 56, 112, 224 pixels, then 128 and 256 channels at 56."""
+    spec = ((64, 28), (64, 56), (64, 112), (64, 224), (128, 56), (256, 56))
+    return [ConvCase(f"case{i + 1}_3x3_{c}_{r}", batch, c, r, r, c, 3, 3, 1, 1, RELU, config=6, sub=i)
+            for i, (c, r) in enumerate(spec)]
+
+
 def trunk_params(batch_seed: int = 0):
     """Synthetic parameters of the ResNet-18-shaped trunk, as plain numpy arrays.
 
