@@ -9,7 +9,7 @@ epilogue.  Weights are packed once before the timed region (the paper fixes them
 after training).  Inputs are seeded synthetic level tensors already resident in
 HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg3|cfg5|quantpack|paper6] [--no-cpu]
 """
 from __future__ import annotations
 
@@ -35,7 +35,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by the same counters' readings for a plain copy of known size (profiles/*.md give the
 # commands, the raw readings and the scale factors 2.000 / 1.000).
-MEASURED_TRAFFIC_BYTES = {"cfg2": int((3096.1 * 2.000 + 25088.0 * 1.000) * 1024), "cfg4": None}
+MEASURED_TRAFFIC_BYTES = {"cfg2": int((3060.7 * 2.000 + 25088.0 * 1.000) * 1024),
+                          "cfg4": int((178421.1 * 2.000 + 262144.1 * 1.000) * 1024)}
 
 
 def parse_args():
@@ -109,7 +110,7 @@ def cpu_baseline_conv(case, seconds_target=12.0):
     t0 = time.perf_counter()
     oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode)
     first = time.perf_counter() - t0
-    reps = max(1, min(20, int(seconds_target / max(first, 1e-3))))
+    reps = max(1, min(100, int(seconds_target / max(first, 1e-3))))
     t0 = time.perf_counter()
     for _ in range(reps):
         oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode)
@@ -118,10 +119,15 @@ def cpu_baseline_conv(case, seconds_target=12.0):
             "kind": "oracle", "sample": f"{reps} full passes of {case.name} (batch {case.B}), {dt:.3f} s each"}
 
 
-def cpu_baseline_gemm(case, rows=64):
+def cpu_baseline_gemm(case, rows=64, seconds_target=12.0):
+    """The oracle on the first rows of the weight matrix against all columns, sized to about seconds_target."""
     import numpy as np
     import oracle
     Lw, La = case.make()
+    t0 = time.perf_counter()
+    oracle.ternary_gemm(np.ascontiguousarray(Lw[:rows]), La, case.act_mode)
+    first = time.perf_counter() - t0
+    rows = int(max(rows, min(case.M, rows * seconds_target / max(first, 1e-3))))
     sub = np.ascontiguousarray(Lw[:rows])
     t0 = time.perf_counter()
     oracle.ternary_gemm(sub, La, case.act_mode)
