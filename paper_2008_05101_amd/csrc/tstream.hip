@@ -466,12 +466,14 @@ constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : CWT
 // rows split into groups of 4 (or 2) leave the last group of every row partly empty.
 constexpr bool has_u7(int R, int CW, int ST) { return R == 3 && ST == 1 && (CW == 8 || CW == 16); }
 
-// Output pixels per group for this call.  FATNN_STREAM_U7=0 switches the groups of seven off.
+// Output pixels per group for this call.  FATNN_STREAM_U7=0 switches the groups of seven off,
+// =2 uses them wherever a kernel exists (for tests of those kernels on small inputs).
 int pick_group_size(int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo, int64_t mblocks) {
-    // groups of seven only where they still give every SIMD two wavefronts of three groups each
-    if (op == OP_TERNARY && has_u7(R, Cw, stride) && Wo % 7 == 0 && out_rows * (Wo / 7) * mblocks >= 6 * 1024) {
+    if (op == OP_TERNARY && has_u7(R, Cw, stride) && Wo % 7 == 0) {
         const char* e = getenv("FATNN_STREAM_U7");
-        if (e == nullptr || e[0] != '0') return 7;
+        const char mode = e == nullptr ? '1' : e[0];
+        // by default only where seven-pixel groups still give every SIMD two wavefronts of three groups
+        if (mode == '2' || (mode != '0' && out_rows * (Wo / 7) * mblocks >= 6 * 1024)) return 7;
     }
     return group_u(R, Cw, stride);
 }

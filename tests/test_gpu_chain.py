@@ -80,6 +80,14 @@ def test_chain_epilogue_exact(Cin, Cout, H, W, R, stride, pad, in_mode, out_mode
     assert torch.equal(Xn, ref)
 
 
+@pytest.mark.parametrize("Cin,Cout,H,W,use_skip", [(256, 256, 7, 7, True), (256, 96, 6, 14, False),
+                                                   (512, 128, 7, 7, True), (512, 64, 4, 14, False)])
+def test_chain_epilogue_groups_of_seven(monkeypatch, Cin, Cout, H, W, use_skip):
+    """The chaining epilogue of the seven-pixel-group kernels (chosen by default only for large batches)."""
+    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+    test_chain_epilogue_exact(Cin, Cout, H, W, 3, 1, 1, 1, 1, 1, use_skip, True)
+
+
 def test_two_layers_chained_equal_the_oracle_pipeline():
     rnd = np.random.default_rng(99)
     B, H, W = 4, 14, 14

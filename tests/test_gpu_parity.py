@@ -247,6 +247,23 @@ def test_conv_parity_small(Cin, Cout, H, W, R, stride, pad, mode, bordered):
     assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, mode))
 
 
+@pytest.mark.parametrize("Cin,Cout,H,W", [(256, 64, 7, 7), (256, 130, 9, 14), (512, 64, 7, 7), (512, 200, 5, 14),
+                                          (256, 64, 3, 21)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_conv_parity_groups_of_seven(monkeypatch, Cin, Cout, H, W, mode):
+    """The seven-pixel-group kernels (normally chosen only for large batches) on small inputs."""
+    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+    rnd = np.random.default_rng(Cin + Cout + H + W + mode)
+    Lw = rnd.integers(0, 3, size=(Cout, 3, 3, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(5, H, W, Cin), dtype=np.int8)
+    scale = rnd.uniform(0.5, 1.5, Cout).astype(np.float32)
+    bias = rnd.standard_normal(Cout).astype(np.float32)
+    Y, Yf = conv_gpu(Lw, Lx, 1, 1, mode, bordered=True, scale=dev(scale), bias=dev(bias))
+    want = oracle.ternary_conv2d(Lw, Lx, 1, 1, mode)
+    assert np.array_equal(Y.cpu().numpy(), want)
+    assert np.array_equal(Yf.cpu().numpy(), oracle.scale_epilogue(want, scale, bias, False))
+
+
 def test_bordered_pack_layout():
     rnd = np.random.default_rng(77)
     B, H, W, C = 2, 5, 4, 64
