@@ -180,6 +180,17 @@ def side_workload(args, torch, fatnn, si, dev):
         hev.close()
         ops = 2.0 * trunk.macs
         kernel_ms = sum(per_layer)
+        # the same pass as one HIP graph submission, and the paper's own setting (whole network, batch 1)
+        side = {}
+        if not args.no_extra:
+            graph = trunk.capture(x)
+            side["graph_replay_ms_per_pass"] = round(time_kernel_ms(torch, graph.replay, 20, 3), 5)
+            t1 = rt.Trunk(blocks, 1, 56, (0.6, 0.7), device=str(dev))
+            x1 = torch.from_numpy(si.trunk_input(1)).to(dev)
+            side["batch1_eager_ms"] = round(time_kernel_ms(torch, lambda: t1.forward(x1), 50, 5), 5)
+            g1 = t1.capture(x1)
+            side["batch1_graph_replay_ms"] = round(time_kernel_ms(torch, g1.replay, 50, 5), 5)
+            side["paper_context_resnet18_batch1_ms"] = {"qualcomm_835": 20.1, "qualcomm_821": 25.2}
         layers = si.cfg3(batch)
         achieved = ops / (kernel_ms * 1e-3) / 1e12
         line = {
@@ -196,7 +207,7 @@ def side_workload(args, torch, fatnn, si, dev):
                          "frac": round(achieved / TERNARY_PEAK_TOPS, 4), "traffic": None,
                          "kernel_ms": round(kernel_ms, 5)},
             "cpu_baseline": None,
-            "extra": {"per_layer_us": {l.name: round(t * 1e3, 2) for l, t in zip(layers, per_layer)},
+            "extra": {**side, "per_layer_us": {l.name: round(t * 1e3, 2) for l, t in zip(layers, per_layer)},
                       "per_layer_tops": {l.name: round(2.0 * l.macs() / (t * 1e-3) / 1e12, 1)
                                          for l, t in zip(layers, per_layer)}},
         }

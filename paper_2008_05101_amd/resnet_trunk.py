@@ -126,3 +126,16 @@ class Trunk:
             k += 3 if sc is not None else 2
             xp, xf = outp, outf
         return xf, xp
+
+    def capture(self, x_static: torch.Tensor) -> "torch.cuda.CUDAGraph":
+        """Records one forward pass on `x_static` into a HIP graph and returns it; `graph.replay()` then
+        re-runs the 20 launches with one submission (at small batch the pass is launch-bound).  The caller
+        refreshes `x_static` in place between replays; the outputs are the tensors `forward` returns.
+        Only the library's own kernels are recorded (no memset nodes, no library reductions)."""
+        self.forward(x_static)          # every one-time host query of the launchers happens outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.graph_out = self.forward(x_static)
+        torch.cuda.synchronize()
+        return graph

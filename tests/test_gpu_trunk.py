@@ -75,3 +75,30 @@ def test_trunk_full_batch_sampled_images():
         assert np.array_equal(f_got[b:b + 1], f_want)
         assert np.array_equal(interior[b:b + 1], L_want)
     assert trunk.macs == sum(c.macs() for c in si.cfg3(batch))
+
+
+def test_trunk_graph_replays_equal_eager_passes():
+    """A captured pass replayed several times, with eager passes and synchronisations in between and a
+    fresh input each time, gives the eager result bit for bit on every replay."""
+    blocks = si.trunk_params()
+    batch, size = 2, 24
+    in_alpha = (0.6, 0.7)
+    trunk = rt.Trunk(to_gpu_blocks(blocks), batch, size, in_alpha, device=DEV)
+    x_static = dev(si.trunk_input(batch, size))
+    graph = trunk.capture(x_static)
+    rnd = np.random.default_rng(7)
+    for rep in range(4):
+        x_new = np.abs(rnd.standard_normal((batch, size, size, 64))).astype(np.float32) * (0.5 + rep)
+        x_static.copy_(dev(x_new))
+        f_e, p_e = trunk.forward(x_static)          # eager pass on the same buffers
+        torch.cuda.synchronize()
+        f_eager, p_eager = f_e.clone(), p_e.clone()
+        f_e.zero_()
+        p_e.zero_()                                  # make sure the replay really rewrites its outputs
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        f_g, p_g = trunk.graph_out
+        assert torch.equal(f_g, f_eager)
+        assert torch.equal(p_g, p_eager)
+        assert float(f_eager.abs().sum()) > 0
