@@ -128,7 +128,9 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     int32_t rc_raw = 0;
     // a missing bias (and a missing skip value below) is -0.0f: x + (-0.0f) == x bit for bit for
     // every x, so the additions need no condition
-    float sc = 0.f, bs = -0.0f;
+    float neg0 = -0.0f;
+    asm volatile("" : "+v"(neg0));   // one register for the constant instead of re-materialising it per use
+    float sc = 0.f, bs = neg0;
     if (OP == OP_TERNARY) rc_raw = p.rowc[m];
     if (EPI == EPI_CHAIN || p.Cf != nullptr) {
         sc = p.scale[m];
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         auto load_skips = [&]() {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                sk[u] = -0.0f;
+                sk[u] = neg0;
                 if (p.skip != nullptr && u < nu)
                     sk[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.skip) +
                                                             (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u));
@@ -322,8 +324,10 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
                 if (p.Cf != nullptr)
                     __builtin_nontemporal_store(f, reinterpret_cast<float*>(reinterpret_cast<char*>(p.Cf) +
                                                                             (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u)));
-                const bool nan = f != f;
-                const uint64_t lo = __ballot((f >= p.t1) || (nan && p.nan_lo != 0u)) & ok_mask;
+                // wave-wide comparisons; a NaN compares false and gets the low bit the quantizer formula gives it
+                uint64_t lo = __ballot(f >= p.t1);
+                if (p.nan_lo != 0u) lo |= __ballot(f != f);
+                lo &= ok_mask;
                 const uint64_t hi = __ballot(f >= p.t2) & ok_mask;
                 // lane 2u <- low halves, lane 2u+1 <- high halves of this pixel's ballots
                 write_lane<2 * u>(wx, (uint32_t)hi);
