@@ -191,7 +191,10 @@ int fatnn_ternary_conv2d(const void *Wp, const void *Xp, int x_layout, int64_t B
  * whose ring must have been initialised once with fatnn_bordered_act_init (the ring is
  * never written here).  Yf (optional, NHWC fp32) receives f, e.g. as the next block's skip
  * input.  skip (optional) is NHWC fp32 [B][Ho][Wo][Cout].  Cout must be a multiple of 32.
- * Shapes the streaming kernel does not cover return FATNN_ERR_UNSUPPORTED.
+ * Shapes the streaming kernel does not cover (filter 1 or 3, stride 1 or 2, Cin in {64, 128,
+ * 256, 512}), and calls whose input, fp32 output or next-layer buffer reaches 4 GiB, return
+ * FATNN_ERR_UNSUPPORTED.  A NaN in f: ReLU turns it into 0 (the maximum of NaN and 0); without
+ * ReLU it is stored as NaN and gets the level the quantizer formula gives a NaN.
  */
 int fatnn_bordered_act_init(void *packed, size_t packed_bytes, int64_t B, int64_t H, int64_t W, int64_t C,
                             int border, int act_mode, void *stream);

@@ -7,6 +7,9 @@ operation, in this order:
 
     f = scale[c] * float(C) ; f = f + bias[c] ; f = f + skip ; f = max(f, 0)
     level = activation quantizer of the next layer applied to f   (oracle/quantizer.py)
+
+The paper does not say what ReLU does to a NaN; the reading taken is the IEEE 754 maximum
+of two numbers, which returns the operand that is not a NaN: max(NaN, 0) = 0.
 """
 from __future__ import annotations
 
@@ -24,6 +27,6 @@ def chain_epilogue(C: np.ndarray, scale: np.ndarray, bias: Optional[np.ndarray],
     if skip is not None:
         f = (f + np.asarray(skip, dtype=np.float32)).astype(np.float32)
     if relu:
-        f = np.maximum(f, np.float32(0))
+        f = np.fmax(f, np.float32(0))
     levels = quantizer.levels_from_floats(f, False, out_act_mode, alpha1, alpha2)
     return f, levels

@@ -88,6 +88,34 @@ def test_chain_epilogue_groups_of_seven(monkeypatch, Cin, Cout, H, W, use_skip):
     test_chain_epilogue_exact(Cin, Cout, H, W, 3, 1, 1, 1, 1, 1, use_skip, True)
 
 
+@pytest.mark.parametrize("relu", [True, False])
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_chain_epilogue_nan_and_inf_in_the_skip(relu, out_mode):
+    rnd = np.random.default_rng(5 + relu + 2 * out_mode)
+    B, Cin, Cout, H, W = 2, 64, 64, 6, 8
+    Lw = rnd.integers(0, 3, size=(Cout, 3, 3, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(B, H, W, Cin), dtype=np.int8)
+    C = oracle.ternary_conv2d(Lw, Lx, 1, 1, 1)
+    scale = (rnd.uniform(0.5, 1.5, Cout) / (float(C.std()) + 1.0)).astype(np.float32)
+    bias = (rnd.standard_normal(Cout) * 0.3).astype(np.float32)
+    skip = (rnd.standard_normal((B, H, W, Cout)) * 0.5).astype(np.float32)
+    flat = skip.reshape(-1)
+    flat[rnd.choice(flat.size, 300, replace=False)] = np.nan
+    flat[rnd.choice(flat.size, 100, replace=False)] = np.inf
+    flat[rnd.choice(flat.size, 100, replace=False)] = -np.inf
+    f_want, lv_want = ochain.chain_epilogue(C, scale, bias, skip, relu, out_mode, 0.6, 0.8)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT, fatnn.OHWI)
+    Xp = fatnn.pack_ternary_bordered(dev(Lx), 1, 1)
+    Xn = fatnn.bordered_act_init(B, H, W, Cout, 1, out_mode, device=DEV)
+    Yf = torch.empty((B, H, W, Cout), dtype=torch.float32, device=DEV)
+    fatnn.ternary_conv2d_chain(Wp, Xp, B, Cin, H, W, Cout, 3, 3, 1, 1, 1, dev(scale), dev(bias), dev(skip), relu,
+                               0.6, 0.8, out_mode, 1, Xn, out_f=Yf)
+    torch.cuda.synchronize()
+    assert np.array_equal(Yf.cpu().numpy(), f_want, equal_nan=True)
+    interior, _, _ = decode_bordered(Xn, B, H, W, Cout, 1)
+    assert np.array_equal(interior, lv_want)
+
+
 def test_two_layers_chained_equal_the_oracle_pipeline():
     rnd = np.random.default_rng(99)
     B, H, W = 4, 14, 14

@@ -104,3 +104,17 @@ def test_chain_epilogue_hand_example():
     f2, lv2 = chain.chain_epilogue(C, scale, bias, None, False, 0, 1.0, 1.0)
     assert f2.reshape(-1).tolist() == [1.0, -0.5, 1.75, 2.25]
     assert lv2.reshape(-1).tolist() == [2, 1, 2, 2]      # Eq. 9: -0.5 is a tie -> 0 -> level 1
+
+
+def test_chain_epilogue_nan_through_relu():
+    # max(NaN, 0) = 0 (the operand that is a number); without ReLU the NaN stays and takes the
+    # level that the literal quantizer formula gives it
+    from oracle import chain
+    C = np.array([[[[4, 4]]]], np.int32)
+    scale = np.array([1.0, 1.0], np.float32)
+    skip = np.array([[[[np.nan, 0.0]]]], np.float32)
+    f, lv = chain.chain_epilogue(C, scale, None, skip, True, 1, 1.0, 1.0)
+    assert f.reshape(-1).tolist() == [0.0, 4.0] and lv.reshape(-1).tolist() == [0, 2]
+    f2, lv2 = chain.chain_epilogue(C, scale, None, skip, False, 1, 1.0, 1.0)
+    assert np.isnan(f2.reshape(-1)[0]) and f2.reshape(-1)[1] == 4.0
+    assert lv2.reshape(-1)[0] == q.levels_from_floats(np.array([np.nan], np.float32), False, 1, 1.0, 1.0)[0]
