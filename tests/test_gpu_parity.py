@@ -264,6 +264,20 @@ def test_conv_parity_groups_of_seven(monkeypatch, Cin, Cout, H, W, mode):
     assert np.array_equal(Yf.cpu().numpy(), oracle.scale_epilogue(want, scale, bias, False))
 
 
+@pytest.mark.parametrize("Cin,Cout,H,W,R,stride,pad", [(64, 70, 12, 10, 3, 2, 1), (128, 130, 7, 7, 3, 1, 1),
+                                                       (64, 128, 14, 14, 1, 2, 0), (256, 64, 7, 9, 1, 1, 0)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_conv_bordered_input_on_the_tiled_kernel(monkeypatch, Cin, Cout, H, W, R, stride, pad, mode):
+    """The fallback that serves bordered inputs the streaming kernel cannot take (tensors of 4 GiB and
+    more): the LDS-tiled kernel reading the bordered layout, forced here on small inputs."""
+    monkeypatch.setenv("FATNN_CONV_KERNEL", "tiled")
+    rnd = np.random.default_rng(Cin + Cout + H + R + stride + mode + 1)
+    Lw = rnd.integers(0, 3, size=(Cout, R, R, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(3, H, W, Cin), dtype=np.int8)
+    Y, _ = conv_gpu(Lw, Lx, stride, pad, mode, bordered=True)
+    assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, mode))
+
+
 def test_bordered_pack_layout():
     rnd = np.random.default_rng(77)
     B, H, W, C = 2, 5, 4, 64
