@@ -23,6 +23,8 @@
 // eight lanes of a group.
 #include "fatnn_device.h"
 
+#include <type_traits>
+
 namespace fatnn {
 namespace {
 
@@ -112,10 +114,15 @@ __device__ __forceinline__ int32_t finalize<OP_TWOBIT_UNIFORM>(const Acc<OP_TWOB
     return 9 * p.K - 2 * acc.s00 - 4 * acc.s01 - 8 * acc.s11;
 }
 
-template <int OP, int WM, int WN, int TM, int TN, bool CONV>
-__global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
-                                                                   const int ntiles) {
-    constexpr int NT = 64 * WM * WN;
+// KS > 1: KS sets of WM x WN wavefronts share one output tile and split the k-words of every
+// stage between them (set s takes k-words s, s + KS, ...); the partial sums meet in LDS at the
+// end.  For problems with fewer tiles than SIMDs it multiplies the wavefronts in flight.
+template <int OP, int WM, int WN, int TM, int TN, bool CONV, int KS = 1>
+__global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
+                                                                        const int ntiles) {
+    constexpr int NT = 64 * WM * WN * KS;
+    static_assert(KT % KS == 0, "the sets split a stage evenly");
+    static_assert(KS == 1 || OP != OP_TWOBIT_UNIFORM, "the LDS reduction handles one accumulator per output");
     constexpr int BM = WM * 8 * TM;
     constexpr int BN = WN * 8 * TN;
     constexpr int LW = (BM * KT) / NT;   // staged word pairs per thread, weights
@@ -151,8 +158,10 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wave_m = wave % WM;
-    const int wave_n = wave / WM;
+    const int ks = KS == 1 ? 0 : wave / (WM * WN);   // k-split set of this wavefront
+    const int wave_in_set = wave - ks * (WM * WN);
+    const int wave_m = wave_in_set % WM;
+    const int wave_n = wave_in_set / WM;
     const int ly = lane >> 3;
     const int lx = lane & 7;
 
@@ -213,8 +222,15 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
         return o;
     };
 
-    plane2 wreg[LW], areg[LA];
-    auto fetch = [&](int kt) {
+    // Small tiles finish a stage faster than a global load returns, so they keep two stages in
+    // flight (two register sets); the large tiles have no registers to spare for that.
+    constexpr bool kTwoAhead = (LW + LA) <= 4;
+    constexpr int NSETS = kTwoAhead ? 2 : 1;
+    plane2 wregs[NSETS][LW], aregs[NSETS][LA];
+    auto fetch = [&](int kt, auto set_tag) {
+        constexpr int set = decltype(set_tag)::value;
+        plane2(&wreg)[LW] = wregs[set];
+        plane2(&areg)[LA] = aregs[set];
         const int kw = kt * KT + ld_j;
         const bool kok = kw < p.Kw;
 #pragma unroll
@@ -242,12 +258,15 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
             for (int i = 0; i < LA; ++i) areg[i] = load2(arsrc, kok ? aoff[i] + (uint32_t)kw * 8u : kOutOfRange);
         }
     };
-    auto stage = [&](int buf) {
+    auto stage = [&](int buf, auto set_tag) {
+        constexpr int set = decltype(set_tag)::value;
 #pragma unroll
-        for (int i = 0; i < LW; ++i) Ws[buf][ld_j][ld_r + i * ROWS_PER_PASS] = wreg[i];
+        for (int i = 0; i < LW; ++i) Ws[buf][ld_j][ld_r + i * ROWS_PER_PASS] = wregs[set][i];
 #pragma unroll
-        for (int i = 0; i < LA; ++i) As[buf][ld_j][ld_r + i * ROWS_PER_PASS] = areg[i];
+        for (int i = 0; i < LA; ++i) As[buf][ld_j][ld_r + i * ROWS_PER_PASS] = aregs[set][i];
     };
+    constexpr std::integral_constant<int, 0> set0{};
+    constexpr std::integral_constant<int, NSETS - 1> set1{};
 
     Acc<OP> acc[TM][TN];
 #pragma unroll
@@ -276,35 +295,79 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
     };
 
     const int nkt = (p.Kw + KT - 1) / KT;
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nkt) fetch(kt + 1);
-        // Fragments of k-word j+1 are read from LDS while k-word j is consumed.  The
-        // scheduling fences keep the compiler from hoisting every LDS read of the stage
-        // to its top (which needs more registers than there are).
+    // One stage of the K loop from LDS buffer buf.  Fragments of k-word j+1 are read from LDS
+    // while k-word j is consumed.  The scheduling fences keep the compiler from hoisting every
+    // LDS read of the stage to its top (which needs more registers than there are).
+    auto compute = [&](int kt, int buf) {
         {
             // jn = k-words of this stage that exist (all KT except in the last, partial stage);
             // the per-word test is a scalar branch
             const int jn = p.Kw - kt * KT;
             plane2 w[2][TM], a[2][TN];
-            read_frag(buf, 0, w[0], a[0]);
+            read_frag(buf, ks, w[0], a[0]);
 #pragma unroll
-            for (int j = 0; j < KT; ++j) {
+            for (int jj = 0; jj < KT / KS; ++jj) {
+                const int j = jj * KS + ks;   // this set's k-word of the stage
                 if (j >= jn) break;
-                if (j + 1 < KT && j + 1 < jn) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+                if (jj + 1 < KT / KS && j + KS < jn) read_frag(buf, j + KS, w[(jj + 1) & 1], a[(jj + 1) & 1]);
                 FATNN_VOP3_RUN_PHASE();
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
+                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[jj & 1][i], a[jj & 1][c]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (kt + 1 < nkt) stage(buf ^ 1);
+    };
+    if constexpr (!kTwoAhead) {
+        fetch(0, set0);
+        stage(0, set0);
         __syncthreads();
+        for (int kt = 0; kt < nkt; ++kt) {
+            const int buf = kt & 1;
+            if (kt + 1 < nkt) fetch(kt + 1, set0);
+            compute(kt, buf);
+            if (kt + 1 < nkt) stage(buf ^ 1, set0);
+            __syncthreads();
+        }
+    } else {
+        // stage kt+1 waits in one register set while stage kt+2 is being loaded into the other
+        fetch(0, set0);
+        if (nkt > 1) fetch(1, set1);
+        stage(0, set0);
+        __syncthreads();
+        for (int kt = 0; kt < nkt; kt += 2) {
+            if (kt + 2 < nkt) fetch(kt + 2, set0);
+            compute(kt, 0);
+            if (kt + 1 < nkt) stage(1, set1);
+            __syncthreads();
+            if (kt + 1 >= nkt) break;
+            if (kt + 3 < nkt) fetch(kt + 3, set1);
+            compute(kt + 1, 1);
+            if (kt + 2 < nkt) stage(0, set0);
+            __syncthreads();
+        }
+    }
+
+    if constexpr (KS > 1) {
+        // partial sums of the sets 1 .. KS-1 go through LDS to set 0 ([set][accumulator][thread of the set])
+        constexpr int SET = 64 * WM * WN;
+        __shared__ int32_t partial[(KS - 1) * TM * TN * SET];
+        const int t = wave_in_set * 64 + lane;
+        if (ks > 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int c = 0; c < TN; ++c) partial[((ks - 1) * TM * TN + i * TN + c) * SET + t] = acc[i][c].v;
+        }
+        __syncthreads();
+        if (ks > 0) return;
+#pragma unroll
+        for (int s2 = 0; s2 < KS - 1; ++s2)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int c = 0; c < TN; ++c) acc[i][c].v += partial[(s2 * TM * TN + i * TN + c) * SET + t];
     }
 
     // ---- epilogue: Eq. 3's subtraction, then the optional fp32 scale -----------------------
@@ -334,7 +397,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
     }
 }
 
-template <int OP, int WM, int WN, int TM, int TN>
+template <int OP, int WM, int WN, int TM, int TN, int KS = 1>
 int launch_shape(const GemmParams& p, hipStream_t stream) {
     constexpr int BM = WM * 8 * TM;
     constexpr int BN = WN * 8 * TN;
@@ -345,10 +408,10 @@ int launch_shape(const GemmParams& p, hipStream_t stream) {
     const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
     const LaunchTiming t = take_launch_timing();
     if (p.is_conv)
-        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true>), dim3(grid), dim3(64 * WM * WN), 0,
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true, KS>), dim3(grid), dim3(64 * WM * WN * KS), 0,
                               stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
     else
-        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false>), dim3(grid), dim3(64 * WM * WN), 0,
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false, KS>), dim3(grid), dim3(64 * WM * WN * KS), 0,
                               stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -362,7 +425,13 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
     const int64_t wave_tiles = (((int64_t)p.M + WTM - 1) / WTM) * (((int64_t)p.N + WTN - 1) / WTN);
     // fewer 64x64 wavefront tiles than SIMDs: quarter-size register tiles, four wavefronts per
     // 64x64 workgroup tile, so that four times as many wavefronts share the work
-    if (wave_tiles < 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
+    if (wave_tiles < 1024) {
+        // still under two wavefronts per SIMD and a long K: two sets of wavefronts per tile split K
+        if constexpr (OP != OP_TWOBIT_UNIFORM) {
+            if (wave_tiles * 4 < 2 * 1024 && p.Kw >= 64) return launch_shape<OP, 2, 2, TM / 2, TN / 2, 2>(p, stream);
+        }
+        return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
+    }
     if (wave_tiles < 4 * 1024) return launch_shape<OP, 1, 1, TM, TN>(p, stream);
     if (p.M <= WTM) return launch_shape<OP, 1, 4, TM, TN>(p, stream);
     return launch_shape<OP, 2, 2, TM, TN>(p, stream);

@@ -137,6 +137,26 @@ def test_gemm_parity_every_workgroup_shape(M, N, K):
     assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, 1))
 
 
+@pytest.mark.parametrize("M,N,K", [(64, 64, 2048), (130, 70, 2100), (200, 300, 2049), (512, 700, 2304), (9, 1000, 4609)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_gemm_parity_split_k_workgroups(M, N, K, mode):
+    # few tiles and a long K: two sets of wavefronts per tile split every K stage and reduce through LDS
+    rnd = np.random.default_rng(M + 3 * N + K + mode)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    scale = si.scale_vec(rnd, M)
+    C, Cf = gemm_gpu(Lw, La, mode, scale=dev(scale))
+    want = oracle.ternary_gemm(Lw, La, mode)
+    assert np.array_equal(C.cpu().numpy(), want)
+    assert np.array_equal(Cf.cpu().numpy(), oracle.scale_epilogue(want, scale, None, True))
+    # the conventional two-bit form through the same workgroup shape
+    code = np.array([0, 1, 3], np.int8)
+    W2 = fatnn.pack_twobit(dev(code[Lw]), fatnn.WEIGHT)
+    A2 = fatnn.pack_twobit(dev(code[La]), fatnn.ACT)
+    C2 = fatnn.twobit_gemm(W2, A2, M, N, K, 0)
+    assert np.array_equal(C2.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
+
+
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 7, 8])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_skinny_gemm_parity(N, mode):
