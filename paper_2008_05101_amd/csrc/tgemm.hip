@@ -416,25 +416,21 @@ int launch_shape(const GemmParams& p, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// Picks the workgroup shape: large square-ish tiles when there is enough work to fill
-// 256 CUs several times over, a tall-skinny tile when M is one wavefront tall, and
-// single-wavefront tiles for small problems.
+// Picks the workgroup shape.  Measured on this chip, the 64 x 64 workgroup tile (four wavefronts
+// of 32 x 32, 4 x 4 accumulators per lane, six wavefronts per SIMD) matches the 128 x 128 tile
+// (8 x 8 accumulators, three per SIMD) up to 8192^3 and beats every larger shape below about
+// 16 K wavefront tiles of 64 x 64, where tile quantisation over 256 CUs matters; the large tile
+// keeps a few per cent on very large problems with a shallow K (fewer operand re-reads).
 template <int OP, int TM, int TN>
 int launch_op(const GemmParams& p, hipStream_t stream) {
     constexpr int WTM = 8 * TM, WTN = 8 * TN;
     const int64_t wave_tiles = (((int64_t)p.M + WTM - 1) / WTM) * (((int64_t)p.N + WTN - 1) / WTN);
-    // fewer 64x64 wavefront tiles than SIMDs: quarter-size register tiles, four wavefronts per
-    // 64x64 workgroup tile, so that four times as many wavefronts share the work
-    if (wave_tiles < 1024) {
-        // still under two wavefronts per SIMD and a long K: two sets of wavefronts per tile split K
-        if constexpr (OP != OP_TWOBIT_UNIFORM) {
-            if (wave_tiles * 4 < 2 * 1024 && p.Kw >= 64) return launch_shape<OP, 2, 2, TM / 2, TN / 2, 2>(p, stream);
-        }
-        return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
+    if (wave_tiles >= 16 * 1024 && p.M > WTM) return launch_shape<OP, 2, 2, TM, TN>(p, stream);
+    // fewer than two wavefronts per SIMD and a long K: two sets of wavefronts per tile split K
+    if constexpr (OP != OP_TWOBIT_UNIFORM) {
+        if (wave_tiles * 4 < 2 * 1024 && p.Kw >= 64) return launch_shape<OP, 2, 2, TM / 2, TN / 2, 2>(p, stream);
     }
-    if (wave_tiles < 4 * 1024) return launch_shape<OP, 1, 1, TM, TN>(p, stream);
-    if (p.M <= WTM) return launch_shape<OP, 1, 4, TM, TN>(p, stream);
-    return launch_shape<OP, 2, 2, TM, TN>(p, stream);
+    return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
 }
 
 }  // namespace

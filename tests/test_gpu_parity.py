@@ -127,9 +127,11 @@ def test_gemm_parity_small_and_ragged(M, N, K, mode):
     assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, mode))
 
 
-@pytest.mark.parametrize("M,N,K", [(2048, 2100, 96), (64, 70000, 64), (2100, 1100, 130), (4096, 8, 300)])
+@pytest.mark.parametrize("M,N,K", [(2048, 2100, 96), (64, 70000, 64), (2100, 1100, 130), (4096, 8, 300),
+                                   (8200, 8300, 40), (64, 1100000, 33)])
 def test_gemm_parity_every_workgroup_shape(M, N, K):
-    # enough 64x64 tiles for the one-wavefront, the 64x256 and the 128x128 workgroup shapes
+    # from a few to more than 16 K tiles of 64x64: the 64x64 and the 128x128 workgroup shapes, and the
+    # one-row-block case that stays on the small shape however many tiles there are
     rnd = np.random.default_rng(M + N + K)
     Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
     La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
