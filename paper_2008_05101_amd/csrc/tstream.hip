@@ -468,7 +468,7 @@ constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : CWT
 
 // Shapes that also have a kernel with groups of seven output pixels: ResNet's 14- and 7-pixel
 // rows split into groups of 4 (or 2) leave the last group of every row partly empty.
-constexpr bool has_u7(int R, int CW, int ST) { return R == 3 && ST == 1 && (CW == 8 || CW == 16); }
+constexpr bool has_u7(int R, int CW, int ST) { return R == 3 && ST == 1 && (CW == 4 || CW == 8 || CW == 16); }
 
 // Output pixels per group for this call.  FATNN_STREAM_U7=0 switches the groups of seven off,
 // =2 uses them wherever a kernel exists (for tests of those kernels on small inputs).
@@ -476,8 +476,10 @@ int pick_group_size(int op, int R, int Cw, int stride, int64_t out_rows, int64_t
     if (op == OP_TERNARY && has_u7(R, Cw, stride) && Wo % 7 == 0) {
         const char* e = getenv("FATNN_STREAM_U7");
         const char mode = e == nullptr ? '1' : e[0];
-        // by default only where seven-pixel groups still give every SIMD two wavefronts of three groups
-        if (mode == '2' || (mode != '0' && out_rows * (Wo / 7) * mblocks >= 6 * 1024)) return 7;
+        // by default only where seven-pixel groups still give every SIMD its wavefronts (two with eight
+        // resident channel words, four with four) three groups each
+        const int64_t enough = 3 * 1024 * (Cw <= 4 ? 4 : 2);
+        if (mode == '2' || (mode != '0' && out_rows * (Wo / 7) * mblocks >= enough)) return 7;
     }
     return group_u(R, Cw, stride);
 }

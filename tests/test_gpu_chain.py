@@ -81,7 +81,8 @@ def test_chain_epilogue_exact(Cin, Cout, H, W, R, stride, pad, in_mode, out_mode
 
 
 @pytest.mark.parametrize("Cin,Cout,H,W,use_skip", [(256, 256, 7, 7, True), (256, 96, 6, 14, False),
-                                                   (512, 128, 7, 7, True), (512, 64, 4, 14, False)])
+                                                   (512, 128, 7, 7, True), (512, 64, 4, 14, False),
+                                                   (128, 128, 5, 28, True), (128, 96, 7, 7, False)])
 def test_chain_epilogue_groups_of_seven(monkeypatch, Cin, Cout, H, W, use_skip):
     """The chaining epilogue of the seven-pixel-group kernels (chosen by default only for large batches)."""
     monkeypatch.setenv("FATNN_STREAM_U7", "2")

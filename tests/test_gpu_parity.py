@@ -270,7 +270,7 @@ def test_conv_parity_small(Cin, Cout, H, W, R, stride, pad, mode, bordered):
 
 
 @pytest.mark.parametrize("Cin,Cout,H,W", [(256, 64, 7, 7), (256, 130, 9, 14), (512, 64, 7, 7), (512, 200, 5, 14),
-                                          (256, 64, 3, 21)])
+                                          (256, 64, 3, 21), (128, 128, 6, 28), (128, 70, 7, 7)])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_conv_parity_groups_of_seven(monkeypatch, Cin, Cout, H, W, mode):
     """The seven-pixel-group kernels (normally chosen only for large batches) on small inputs."""
