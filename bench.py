@@ -191,6 +191,20 @@ def side_workload(args, torch, fatnn, si, dev):
             g1 = t1.capture(x1)
             side["batch1_graph_replay_ms"] = round(time_kernel_ms(torch, g1.replay, 50, 5), 5)
             side["paper_context_resnet18_batch1_ms"] = {"qualcomm_835": 20.1, "qualcomm_821": 25.2}
+            del t1, g1
+            # the paper's second network: ResNet-34 shape (16 blocks, 35 ternary convolutions)
+            blocks34 = [rt.BlockParams(cv(b["conv1"]), cv(b["conv2"]),
+                                       None if b["shortcut"] is None else cv(b["shortcut"]))
+                        for b in si.trunk_params(34)]
+            t34 = rt.Trunk(blocks34, batch, 56, (0.6, 0.7), device=str(dev))
+            ms34 = time_kernel_ms(torch, lambda: t34.forward(x), 10, 2)
+            side["resnet34_batch64_ms_per_pass"] = round(ms34, 5)
+            side["resnet34_batch64_tops"] = round(2.0 * t34.macs / (ms34 * 1e-3) / 1e12, 1)
+            del t34
+            t34b1 = rt.Trunk(blocks34, 1, 56, (0.6, 0.7), device=str(dev))
+            g34 = t34b1.capture(x1)
+            side["resnet34_batch1_graph_replay_ms"] = round(time_kernel_ms(torch, g34.replay, 50, 5), 5)
+            side["paper_context_resnet34_batch1_ms"] = {"qualcomm_835": 42.1, "qualcomm_821": 51.4}
         layers = si.cfg3(batch)
         achieved = ops / (kernel_ms * 1e-3) / 1e12
         line = {

@@ -195,37 +195,54 @@ def paper_six(batch: int = 1) -> List[ConvCase]:
             for i, (c, r) in enumerate(spec)]
 
 
-def trunk_params(batch_seed: int = 0):
-    """Synthetic parameters of the ResNet-18-shaped trunk, as plain numpy arrays.
+def trunk_blocks(depth: int = 18):
+    """(Cin, Cout, stride) of the basic blocks after the stem for ResNet-18 or ResNet-34."""
+    counts = {18: (2, 2, 2, 2), 34: (3, 4, 6, 3)}[depth]
+    out = []
+    cin = 64
+    for stage, n in enumerate(counts):
+        cout = 64 << stage
+        for i in range(n):
+            out.append((cin, cout, 2 if (i == 0 and stage > 0) else 1))
+            cin = cout
+    return tuple(out)
+
+
+def trunk_params(depth: int = 18):
+    """Synthetic parameters of the ResNet-18- (or ResNet-34-) shaped trunk, as plain numpy arrays.
 
     Returns a list of blocks; each block is a dict with conv1, conv2 and (for down-sampling blocks)
-    shortcut, each a dict: levels OHWI int8, scale, bias fp32, alpha (a1, a2), stride.  Layer shapes
-    and weight seeds are those of cfg3's layer list.
+    shortcut, each a dict: levels OHWI int8, scale, bias fp32, alpha (a1, a2), stride.  For depth 18 the
+    layer shapes and weight seeds are those of cfg3's layer list; deeper trunks continue the numbering.
     """
-    layers = cfg3(batch=1)
-    blocks_spec = ((64, 64, 1), (64, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2), (256, 256, 1),
-                   (256, 512, 2), (512, 512, 1))
     out = []
     li = 0
+    hw = 56
 
-    def conv(case: "ConvCase", idx: int):
-        lw = levels(rng_for(3, TENSOR_W, idx), (case.Cout, case.R, case.S, case.Cin), case.w_probs)
+    def conv(cin: int, cout: int, ks: int, stride: int, idx: int):
+        k = ks * ks * cin
+        lw = levels(rng_for(3, TENSOR_W, idx), (cout, ks, ks, cin))
         r = rng_for(3, TENSOR_SCALE, idx)
-        scale = (r.uniform(0.5, 1.5, size=case.Cout) / np.sqrt(case.K)).astype(np.float32)
-        bias = (rng_for(3, TENSOR_BIAS, idx).standard_normal(case.Cout) * 0.3).astype(np.float32)
-        alpha = (float(np.float32(0.7 + 0.01 * idx)), float(np.float32(0.9 - 0.01 * idx)))
-        return {"levels": lw, "scale": scale, "bias": bias, "alpha": alpha, "stride": case.stride}
+        scale = (r.uniform(0.5, 1.5, size=cout) / np.sqrt(k)).astype(np.float32)
+        bias = (rng_for(3, TENSOR_BIAS, idx).standard_normal(cout) * 0.3).astype(np.float32)
+        a = 0.01 * (idx % 19)
+        alpha = (float(np.float32(0.7 + a)), float(np.float32(0.9 - a)))
+        return {"levels": lw, "scale": scale, "bias": bias, "alpha": alpha, "stride": stride}
 
-    for cin, cout, stride in blocks_spec:
-        blk = {"conv1": conv(layers[li], li), "conv2": conv(layers[li + 1], li + 1), "shortcut": None}
-        assert layers[li].Cin == cin and layers[li].Cout == cout and layers[li].stride == stride
+    for cin, cout, stride in trunk_blocks(depth):
+        blk = {"conv1": conv(cin, cout, 3, stride, li), "conv2": conv(cout, cout, 3, 1, li + 1), "shortcut": None}
         li += 2
         if stride != 1 or cin != cout:
-            assert layers[li].R == 1 and layers[li].Cin == cin and layers[li].Cout == cout
-            blk["shortcut"] = conv(layers[li], li)
+            blk["shortcut"] = conv(cin, cout, 1, stride, li)
             li += 1
         out.append(blk)
-    assert li == len(layers)
+        hw //= stride
+    if depth == 18:
+        layers = cfg3(batch=1)
+        assert li == len(layers)
+        flat = [c for b in out for c in ([b["conv1"], b["conv2"]] + ([b["shortcut"]] if b["shortcut"] else []))]
+        for c, case in zip(flat, layers):
+            assert c["levels"].shape == (case.Cout, case.R, case.S, case.Cin) and c["stride"] == case.stride
     return out
 
 

@@ -102,3 +102,22 @@ def test_trunk_graph_replays_equal_eager_passes():
         assert torch.equal(f_g, f_eager)
         assert torch.equal(p_g, p_eager)
         assert float(f_eager.abs().sum()) > 0
+
+
+def test_resnet34_shaped_trunk_matches_oracle_pipeline():
+    """The deeper of the paper's two ImageNet networks (16 basic blocks, 35 ternary convolutions)."""
+    blocks = si.trunk_params(34)
+    assert len(blocks) == 16
+    batch, size = 1, 24
+    x = si.trunk_input(batch, size)
+    in_alpha = (0.6, 0.7)
+    f_want, L_want = oracle_trunk(blocks, x, in_alpha)
+    trunk = rt.Trunk(to_gpu_blocks(blocks), batch, size, in_alpha, device=DEV)
+    seen = []
+    f_got, p_got = trunk.forward(dev(x), before_conv=seen.append)
+    torch.cuda.synchronize()
+    assert sorted(seen) == list(range(35))
+    assert np.array_equal(f_got.cpu().numpy(), f_want)
+    interior, _, _ = decode_bordered(p_got, batch, f_want.shape[1], f_want.shape[2], 512, 1)
+    assert np.array_equal(interior, L_want)
+    assert len(np.unique(L_want)) >= 2
