@@ -129,7 +129,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     // a missing bias (and a missing skip value below) is -0.0f: x + (-0.0f) == x bit for bit for
     // every x, so the additions need no condition
     float neg0 = -0.0f;
-    asm volatile("" : "+v"(neg0));   // one register for the constant instead of re-materialising it per use
+    // one register for the constant instead of re-materialising it per use, where registers are not scarce
+    if constexpr (CW < 8) asm volatile("" : "+v"(neg0));
     float sc = 0.f, bs = neg0;
     if (OP == OP_TERNARY) rc_raw = p.rowc[m];
     if (EPI == EPI_CHAIN || p.Cf != nullptr) {
