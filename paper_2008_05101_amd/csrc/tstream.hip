@@ -410,10 +410,13 @@ int resident_waves_per_simd(Kernel kernel, int wpb, size_t lds, int* cache) {
 // should see enough groups to amortise loading its weights.  FATNN_STREAM_WPS sets the
 // wavefronts per SIMD (for measurements).
 int plan_ranges(int64_t mblocks, int64_t ngroups, int occ, int64_t max_groups_per_range) {
-    // as many wavefronts per SIMD as stay resident (up to 6: more only adds weight-load traffic
-    // at the start), but at least three pixel groups per wavefront
+    // As many wavefronts per SIMD as stay resident, up to 6 (more only adds weight-load traffic at
+    // the start); beyond four only while each still gets three pixel groups, and never more
+    // wavefronts than groups.  (One or two wavefronts per SIMD issue the logic/popcount pairs at
+    // 0.6x / 1.1x the nominal rate, four at 1.2x: small problems want the wavefronts, not the groups.)
     int64_t wps = occ < 6 ? occ : 6;
-    while (wps > 1 && ngroups * mblocks < 3 * 1024 * wps) --wps;
+    while (wps > 4 && ngroups * mblocks < 3 * 1024 * wps) --wps;
+    while (wps > 1 && ngroups * mblocks < 1024 * wps) --wps;
     const char* e = getenv("FATNN_STREAM_WPS");
     if (e != nullptr && atoi(e) > 0) {
         wps = atoi(e);
