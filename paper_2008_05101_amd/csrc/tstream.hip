@@ -470,20 +470,25 @@ constexpr int group_u(int R, int CW, int ST) {
 // Channel words kept in registers per pass: everything, except for 3x3 filters over 512 channels.
 constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : CWT; }
 
-// Shapes that also have a kernel with groups of seven output pixels: ResNet's 14- and 7-pixel
-// rows split into groups of 4 (or 2) leave the last group of every row partly empty.
-constexpr bool has_u7(int R, int CW, int ST) { return R == 3 && ST == 1 && (CW == 4 || CW == 8 || CW == 16); }
+// Second group size of a shape (0 = none).  ResNet's rows are 56, 28, 14 and 7 pixels wide: groups of
+// seven leave no partly empty group at the end of a row.  (For 64-channel layers groups of fourteen
+// were measured 3-5 % slower than the groups of eight, which already divide 56.)
+constexpr int alt_u(int R, int CW, int ST) {
+    if (R != 3 || ST != 1) return 0;
+    return (CW == 4 || CW == 8 || CW == 16) ? 7 : 0;
+}
 
-// Output pixels per group for this call.  FATNN_STREAM_U7=0 switches the groups of seven off,
-// =2 uses them wherever a kernel exists (for tests of those kernels on small inputs).
+// Output pixels per group for this call.  FATNN_STREAM_U7=0 switches the second group size off,
+// =2 uses it wherever a kernel exists (for tests of those kernels on small inputs).
 int pick_group_size(int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo, int64_t mblocks) {
-    if (op == OP_TERNARY && has_u7(R, Cw, stride) && Wo % 7 == 0) {
+    const int alt = alt_u(R, Cw, stride);
+    if (op == OP_TERNARY && alt != 0 && Wo % alt == 0) {
         const char* e = getenv("FATNN_STREAM_U7");
         const char mode = e == nullptr ? '1' : e[0];
-        // by default only where seven-pixel groups still give every SIMD its wavefronts (two with eight
-        // resident channel words, four with four) three groups each
+        // by default only where the larger groups still give every SIMD its wavefronts (two with eight
+        // resident channel words, four otherwise) three groups each
         const int64_t enough = 3 * 1024 * (Cw <= 4 ? 4 : 2);
-        if (mode == '2' || (mode != '0' && out_rows * (Wo / 7) * mblocks >= enough)) return 7;
+        if (mode == '2' || (mode != '0' && out_rows * (Wo / alt) * mblocks >= enough)) return alt;
     }
     return group_u(R, Cw, stride);
 }
@@ -505,8 +510,9 @@ int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride,
     if (R == RR && Cw == CC && stride == SS) {                                                                 \
         constexpr int UU = group_u(RR, CC, SS);                                                                \
         constexpr int RC = resident_cw(RR, CC);                                                                \
-        if constexpr (has_u7(RR, CC, SS)) {                                                                    \
-            if (U == 7) return launch_inst<OP_TERNARY, RR, RC, CC, SS, 7>(p, out_rows, Wo, stream);            \
+        if constexpr (alt_u(RR, CC, SS) != 0) {                                                                \
+            if (U == alt_u(RR, CC, SS))                                                                        \
+                return launch_inst<OP_TERNARY, RR, RC, CC, SS, alt_u(RR, CC, SS)>(p, out_rows, Wo, stream);    \
         }                                                                                                      \
         if (op == OP_TERNARY) return launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);    \
         if (op == OP_XOR_PAIR) return launch_inst<OP_XOR_PAIR, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);  \
