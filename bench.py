@@ -42,15 +42,24 @@ MEASURED_TRAFFIC_BYTES = {"cfg2": int((3060.7 * 2.000 + 25088.0 * 1.000) * 1024)
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default depends on the workload)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed warm-up steps")
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg3", "cfg5", "quantpack", "paper6"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE "
                          "counters of a rocprofv3 --pmc run) and exit")
-    return ap.parse_args()
+    args = ap.parse_args()
+    # Defaults long enough for the clocks to settle (a cfg2 step is 23 us: 200 steps were over before the GPU
+    # had reached its sustained clock, and read 6 % slow), short enough to finish in seconds.
+    steps, warmup = {"cfg2": (4000, 1000), "cfg4": (100, 20), "cfg3": (200, 50), "cfg5": (50, 10),
+                     "quantpack": (100, 20), "paper6": (20, 3)}[args.workload]
+    if args.steps is None:
+        args.steps = steps
+    if args.warmup is None:
+        args.warmup = warmup
+    return args
 
 
 def time_kernel_ms(torch, fn, iters, warmup):
@@ -65,6 +74,28 @@ def time_kernel_ms(torch, fn, iters, warmup):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / iters
+
+
+def time_graph_ms(torch, fn, iters, replays=5):
+    """Average duration of fn's launches with the host out of the picture: `iters` calls recorded into one
+    HIP graph (library kernels only), replayed `replays` times."""
+    fn()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(iters):
+            fn()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (iters * replays)
 
 
 class HipEvents:
@@ -246,13 +277,14 @@ def side_workload(args, torch, fatnn, si, dev):
                 X2 = fatnn.pack_twobit_bordered(code[Lx_d.long()], case.pad)
                 Y = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.int32, device=dev)
                 a = (case.B, case.Cin, case.H, case.W, case.Cout, case.R, case.S, case.stride, case.pad)
-                n, w = args.steps, args.warmup
-                t_ter = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *a, case.act_mode, out=Y,
-                                                                           x_layout=fatnn.X_BORDERED), n, w)
-                t_two = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *a, out=Y,
-                                                                          x_layout=fatnn.X_BORDERED), n, w)
-                t_xn = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *a, fatnn.BASIS_XNOR_ONLY, out=Y,
-                                                                         x_layout=fatnn.X_BORDERED), n, w)
+                # launches recorded into a HIP graph: at batch 1 a Python call costs more than the kernel
+                n = args.steps
+                t_ter = time_graph_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *a, case.act_mode, out=Y,
+                                                                          x_layout=fatnn.X_BORDERED), n)
+                t_two = time_graph_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *a, out=Y,
+                                                                         x_layout=fatnn.X_BORDERED), n)
+                t_xn = time_graph_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *a, fatnn.BASIS_XNOR_ONLY, out=Y,
+                                                                        x_layout=fatnn.X_BORDERED), n)
                 ops = 2.0 * case.macs()
                 results[f"{case.name}_b{batch}"] = {
                     "ternary_us": round(t_ter * 1e3, 2), "twobit_us": round(t_two * 1e3, 2),
@@ -534,18 +566,22 @@ def main():
     # ---- side measurements (outside the timed region) ---------------------------------------
     if not args.no_extra:
         try:
-            extra["pack_ms"] = round(time_kernel_ms(torch, pack_step, 50, 5), 5)
-            extra["main_kernel_ms_back_to_back"] = round(time_kernel_ms(torch, main_kernel, 50, 5), 5)
+            reps = (500, 100) if args.workload == "cfg2" else (20, 5)
+            extra["pack_ms"] = round(time_kernel_ms(torch, pack_step, *reps), 5)
+            extra["main_kernel_ms_back_to_back"] = round(time_kernel_ms(torch, main_kernel, *reps), 5)
+            # the same step and the same kernel replayed from a HIP graph (no host launch path between them)
+            extra["step_ms_graph_replay"] = round(time_graph_ms(torch, step, 20), 5)
+            extra["main_kernel_ms_graph_replay"] = round(time_graph_ms(torch, main_kernel, 20), 5)
             code = torch.tensor([0, 1, 3], dtype=torch.int8, device=dev)
             if args.workload == "cfg2":
                 W2 = fatnn.pack_twobit(code[Lw_d.long()], fatnn.WEIGHT, fatnn.OHWI)
                 X2 = fatnn.pack_twobit_bordered(code[Lx_d.long()], case.pad)
                 t2 = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *conv_args[:-1], out=Y,
-                                                                       x_layout=fatnn.X_BORDERED), 50, 5)
+                                                                       x_layout=fatnn.X_BORDERED), 500, 100)
                 t3 = time_kernel_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y,
-                                                                        x_layout=fatnn.X_BORDERED), 50, 5)
+                                                                        x_layout=fatnn.X_BORDERED), 500, 100)
                 t4 = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *conv_args[:-1], fatnn.BASIS_XNOR_ONLY,
-                                                                       out=Y, x_layout=fatnn.X_BORDERED), 50, 5)
+                                                                       out=Y, x_layout=fatnn.X_BORDERED), 500, 100)
                 extra["twobit_conv_ms"] = round(t2, 5)
                 extra["ternary_conv_int32_only_ms"] = round(t3, 5)
                 extra["speedup_vs_twobit"] = round(t2 / t3, 3)
