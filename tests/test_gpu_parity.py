@@ -159,6 +159,22 @@ def test_gemm_parity_split_k_workgroups(M, N, K, mode):
     assert np.array_equal(C2.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
 
 
+@pytest.mark.parametrize("M,N,K", [(3, 5, 100003), (70, 9, 262144 + 17), (2, 40, 1 << 20)])
+def test_gemm_parity_very_long_k(M, N, K):
+    # thousands of K stages per tile; all-(+1) rows and columns make the sums reach +-K and 2K
+    rnd = np.random.default_rng(K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    Lw[0, :] = 2
+    La[0, :] = 2
+    La[1, :] = 0
+    for mode in (0, 1):
+        C, _ = gemm_gpu(Lw, La, mode)
+        want = oracle.ternary_gemm(Lw, La, mode)
+        assert np.array_equal(C.cpu().numpy(), want)
+        assert want[0, 0] == (K if mode == 0 else 2 * K) and want[0, 1] == (-K if mode == 0 else 0)
+
+
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 7, 8])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_skinny_gemm_parity(N, mode):
