@@ -237,6 +237,17 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     // i comes BEFORE batch i+1 is issued.  PAR = which buffer holds batch 0.
     auto run_group = [&](auto par_tag, int gi) {
         constexpr int PAR = decltype(par_tag)::value;
+        // The SIMD's arbiter favours its oldest wavefront, so the wavefronts of a SIMD would finish
+        // one after the other and the last would run its final groups alone, at half the issue rate.
+        // A wavefront lowers its own priority as it nears its end: the ones behind catch up and all
+        // finish together.
+        {
+            const int left = (NPASS - 1 - pass) * count + (count - gi);   // groups still to do, this one included
+            if (left >= 4) __builtin_amdgcn_s_setprio(3);
+            else if (left == 3) __builtin_amdgcn_s_setprio(2);
+            else if (left == 2) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         const uint32_t o0 = ooff, n0 = noff;
         const int nu = (wg == wgroups - 1) ? p.tailU : U;   // output pixels of this group that exist
         uint32_t goff_next = goff;
