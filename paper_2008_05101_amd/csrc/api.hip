@@ -227,6 +227,7 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
         q.M = (int32_t)Cout;
         q.Kw = (int32_t)(cs.K / 32);
         q.C = Y; q.Cf = Yf; q.ldc = (int32_t)Cout;
+        q.out_bytes = (uint32_t)out_bytes;
         q.scale = scale; q.bias = bias;
         q.Hp = (int32_t)Hs; q.Wp = (int32_t)Ws; q.Ho = (int32_t)cs.Ho;
         q.xoff = xb - pad;

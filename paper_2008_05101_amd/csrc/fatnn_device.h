@@ -103,6 +103,7 @@ struct StreamParams {
     int32_t* C;
     float* Cf;
     int32_t ldc;            // elements between consecutive output pixels (= output channels)
+    uint32_t out_bytes;     // size of each output tensor in bytes (below 4 GiB)
     const float* scale;
     const float* bias;
     int32_t Hp, Wp, Ho;     // bordered input height / width, output height

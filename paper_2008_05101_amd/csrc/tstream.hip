@@ -226,6 +226,12 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     uint32_t buf[2][Sh::BUF];
     int pass = 0;
     const uint32_t lane_out = (uint32_t)m;   // this lane's channel inside an output pixel
+    const uint32_t lane_byte = lane_out * 4u;
+    // raw buffer resources over the two outputs (the host guarantees they are below 4 GiB)
+    constexpr int kRsrcFlags = 0x00020000;
+    constexpr int kStreamOut = 2;            // non-temporal
+    const __amdgpu_buffer_rsrc_t crsrc = __builtin_amdgcn_make_buffer_rsrc(p.C, 0, (int)p.out_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t frsrc = __builtin_amdgcn_make_buffer_rsrc(p.Cf, 0, (int)p.out_bytes, kRsrcFlags);
     // Chaining epilogue: lane 2u+h stores half h (channels 32h..32h+31 of this wavefront's 64)
     // of output pixel u as one word pair of the next layer's input.
     const uint32_t xn_word = (uint32_t)(2 * mb + (lane & 1));
@@ -357,21 +363,34 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
                 *reinterpret_cast<plane2*>(reinterpret_cast<char*>(p.Xn) + (size_t)(n0 * 8u + xn_lane_off)) = word;
             }
         } else {
-            {
+            // Outputs go through buffer resources: the address of a store is (resource base) + (lane's
+            // channel, a constant VGPR) + (pixel offset, an SGPR), so no vector instruction computes
+            // addresses.  They are written once and not read again by this kernel: streamed out.
+            // Which outputs exist and whether the group is complete is decided once per group.
+            auto emit = [&](auto has_c, auto has_f, auto full) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    if (u >= nu) break;
+                    if (!decltype(full)::value && u >= nu) break;
                     const int32_t v = (OP == OP_TERNARY) ? rc - acc[u] : (OP == OP_XOR_PAIR ? p.K - p.cmul * acc[u] : p.K - (acc[u] >> 1));
-                    const size_t ob = (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u);
-                    // outputs are written once and not read again by this kernel: stream them out
-                    if (p.C != nullptr)
-                        __builtin_nontemporal_store(v, reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.C) + ob));
-                    if (p.Cf != nullptr) {
+                    const int soff = (int)((o0 + (uint32_t)u * ldc) * 4u);
+                    if constexpr (decltype(has_c)::value)
+                        __builtin_amdgcn_raw_buffer_store_b32((uint32_t)v, crsrc, (int)lane_byte, soff, kStreamOut);
+                    if constexpr (decltype(has_f)::value) {
                         float f = sc * (float)v;
                         f = f + bs;
-                        __builtin_nontemporal_store(f, reinterpret_cast<float*>(reinterpret_cast<char*>(p.Cf) + ob));
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(f), frsrc, (int)lane_byte, soff, kStreamOut);
                     }
                 }
+            };
+            constexpr std::true_type yes{};
+            constexpr std::false_type no{};
+            const bool full = nu == U;
+            if (p.C != nullptr && p.Cf != nullptr) {
+                if (full) emit(yes, yes, yes); else emit(yes, yes, no);
+            } else if (p.C != nullptr) {
+                if (full) emit(yes, no, yes); else emit(yes, no, no);
+            } else {
+                if (full) emit(no, yes, yes); else emit(no, yes, no);
             }
         }
     };
