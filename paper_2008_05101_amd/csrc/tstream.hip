@@ -229,7 +229,10 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     const uint32_t lane_byte = lane_out * 4u;
     // raw buffer resources over the two outputs (the host guarantees they are below 4 GiB)
     constexpr int kRsrcFlags = 0x00020000;
-    constexpr int kStreamOut = 2;            // non-temporal
+    // cache policy of the output stores: device scope (sc1) + non-temporal (nt).  Measured: plain stores
+    // 20.1 us on the 128-channel layer and 97 us on the 64 -> 256 1x1 layer, nt alone 19.2 / 84, sc1 alone
+    // 18.3 / 81 but the kernel after it slows down, both together 18.3 / 84 with no such after-effect.
+    constexpr int kStreamOut = 16 | 2;
     const __amdgpu_buffer_rsrc_t crsrc = __builtin_amdgcn_make_buffer_rsrc(p.C, 0, (int)p.out_bytes, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t frsrc = __builtin_amdgcn_make_buffer_rsrc(p.Cf, 0, (int)p.out_bytes, kRsrcFlags);
     // Chaining epilogue: lane 2u+h stores half h (channels 32h..32h+31 of this wavefront's 64)
