@@ -235,6 +235,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     constexpr int kStreamOut = 16 | 2;
     const __amdgpu_buffer_rsrc_t crsrc = __builtin_amdgcn_make_buffer_rsrc(p.C, 0, (int)p.out_bytes, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t frsrc = __builtin_amdgcn_make_buffer_rsrc(p.Cf, 0, (int)p.out_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t srsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.skip), 0, (int)p.out_bytes, kRsrcFlags);
     // Chaining epilogue: lane 2u+h stores half h (channels 32h..32h+31 of this wavefront's 64)
     // of output pixel u as one word pair of the next layer's input.
     const uint32_t xn_word = (uint32_t)(2 * mb + (lane & 1));
@@ -292,8 +294,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
             for (int u = 0; u < U; ++u) {
                 sk[u] = neg0;
                 if (p.skip != nullptr && u < nu)
-                    sk[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.skip) +
-                                                            (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u));
+                    sk[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                        srsrc, (int)lane_byte, (int)((o0 + (uint32_t)u * ldc) * 4u), 0));
             }
         };
         if constexpr (EPI == EPI_CHAIN && kSkipEarly) {
@@ -343,8 +345,8 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
                     asm volatile("" : "+v"(f));   // keeps this a scalar branch instead of a per-lane select
                 }
                 if (p.Cf != nullptr)
-                    __builtin_nontemporal_store(f, reinterpret_cast<float*>(reinterpret_cast<char*>(p.Cf) +
-                                                                            (size_t)((o0 + (uint32_t)u * ldc + lane_out) * 4u)));
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(f), frsrc, (int)lane_byte,
+                                                          (int)((o0 + (uint32_t)u * ldc) * 4u), kStreamOut);
                 // wave-wide comparisons; a NaN compares false and gets the low bit the quantizer formula gives it
                 uint64_t lo = __ballot(f >= p.t1);
                 if (p.nan_lo != 0u) lo |= __ballot(f != f);
