@@ -371,6 +371,9 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const 
     }
 
     // ---- epilogue: Eq. 3's subtraction, then the optional fp32 scale -----------------------
+    // (column n = col0 + wcol + ... is even, so a pair is 8-byte aligned when the row pitch and the base are)
+    const bool pair_c = p.ldc_n == 1 && (p.ldc_m & 1) == 0 && (reinterpret_cast<uintptr_t>(p.C) & 7) == 0;
+    const bool pair_f = p.ldf_n == 1 && (p.ldf_m & 1) == 0 && (reinterpret_cast<uintptr_t>(p.Cf) & 7) == 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = row0 + wrow + (i >> 1) * 16 + (i & 1);
@@ -382,16 +385,42 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const 
             sc = p.scale[m];
             if (p.bias != nullptr) bs = p.bias[m];
         }
+        // A lane's columns come in adjacent pairs (c, c+1): where the output is column-contiguous and
+        // 8-byte aligned the pair is one 64-bit store.  (Plain stores: a wavefront writes 64-byte pieces of
+        // rows, which L2 merges with the neighbouring wavefront's; non-temporal stores were 10-15 % slower.)
 #pragma unroll
-        for (int c = 0; c < TN; ++c) {
-            const int n = col0 + wcol + (c >> 1) * 16 + (c & 1);
+        for (int c = 0; c < TN; c += 2) {
+            const int n = col0 + wcol + (c >> 1) * 16;
             if (n >= p.N) continue;
-            const int32_t v = finalize<OP>(acc[i][c], p, rc);
-            if (p.C != nullptr) p.C[(int64_t)m * p.ldc_m + (int64_t)n * p.ldc_n] = v;
+            const int32_t v0 = finalize<OP>(acc[i][c], p, rc);
+            const int32_t v1 = finalize<OP>(acc[i][c + 1], p, rc);
+            const bool two = n + 1 < p.N;
+            if (p.C != nullptr) {
+                int32_t* dst = p.C + ((int64_t)m * p.ldc_m + (int64_t)n * p.ldc_n);
+                if (pair_c && two) {
+                    typedef int32_t i32x2 __attribute__((ext_vector_type(2)));
+                    const i32x2 v = {v0, v1};
+                    *reinterpret_cast<i32x2*>(dst) = v;
+                } else {
+                    dst[0] = v0;
+                    if (two) dst[p.ldc_n] = v1;
+                }
+            }
             if (p.Cf != nullptr) {
-                float f = __fmul_rn(sc, (float)v);
-                if (p.bias != nullptr) f = __fadd_rn(f, bs);
-                p.Cf[(int64_t)m * p.ldf_m + (int64_t)n * p.ldf_n] = f;
+                float f0 = __fmul_rn(sc, (float)v0), f1 = __fmul_rn(sc, (float)v1);
+                if (p.bias != nullptr) {
+                    f0 = __fadd_rn(f0, bs);
+                    f1 = __fadd_rn(f1, bs);
+                }
+                float* dst = p.Cf + ((int64_t)m * p.ldf_m + (int64_t)n * p.ldf_n);
+                if (pair_f && two) {
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    const f32x2 v = {f0, f1};
+                    *reinterpret_cast<f32x2*>(dst) = v;
+                } else {
+                    dst[0] = f0;
+                    if (two) dst[p.ldf_n] = f1;
+                }
             }
         }
     }
