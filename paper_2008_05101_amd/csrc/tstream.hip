@@ -165,12 +165,15 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     uint32_t goff;              // byte offset of the group's first strip in the bordered input
     uint32_t ooff;              // element offset of the group's first output pixel, channel 0
     uint32_t noff = 0;          // word-pair offset of that pixel in the next layer's bordered input
-    // 1x1 filters: a wavefront takes every nranges-th group instead of a contiguous block, so that
+    // 1x1 filters (and the 3x3 shapes listed below): a wavefront takes every nranges-th group instead
+    // of a contiguous block, so that
     // all wavefronts move through the output as one compact front.  These layers are bound by
     // writing their output, and 1000 separate write streams reach 5.0 TB/s on this chip where a
     // compact front reaches 5.9 (measured with a store-only kernel of the same pattern); with a
     // 1x1 filter neighbouring groups share no input, so nothing is lost on the read side.
-    constexpr bool kStrided = R == 1 && ST == 1;   // (the small stride-2 shortcut layers measured no better)
+    // Measured per shape: it also pays for the 64-channel 3x3 layers (35.5 -> 33 us, stride 2: 21.2 -> 18.4)
+    // and a little for the 128-channel stride-1 ones; the 256-channel layers lose 2-3 us with it.
+    constexpr bool kStrided = (R == 1 && ST == 1) || (R == 3 && (CW == 2 || (CW == 4 && ST == 1)));
     int img = 0;                // image of the current group (strided walk only)
     const int Wo = (wgroups - 1) * U + p.tailU;
     auto locate = [&]() {       // offsets of group (img, ho, wg)
