@@ -553,9 +553,9 @@ int pick_group_size(int op, int R, int Cw, int stride, int64_t out_rows, int64_t
     if (op == OP_TERNARY && alt != 0 && Wo % alt == 0) {
         const char* e = getenv("FATNN_STREAM_U7");
         const char mode = e == nullptr ? '1' : e[0];
-        // by default only where the larger groups still give every SIMD its wavefronts (two with eight
-        // resident channel words, four otherwise) three groups each
-        const int64_t enough = 3 * 1024 * (Cw <= 4 ? 4 : 2);
+        // by default only where the larger groups still leave every SIMD three of them with eight resident
+        // channel words (measured down to 3.5 per SIMD: 512 channels at 7x7, batch 64) and twelve otherwise
+        const int64_t enough = 1024 * (Cw <= 4 ? 12 : 3);
         if (mode == '2' || (mode != '0' && out_rows * (Wo / alt) * mblocks >= enough)) return alt;
     }
     return group_u(R, Cw, stride);
