@@ -69,7 +69,8 @@ __device__ __forceinline__ void sload_run(const sptr_t src, uint32_t* dst) {
     }
 }
 
-// CW = channel words resident per pass, CWT = channel words per stored pixel (CWT = CW * passes).
+// CW = channel words one wavefront keeps resident, CWT = channel words per stored pixel (CWT = CW * wavefronts
+// sharing a row block).
 template <int R, int CW, int ST, int U>
 struct StreamShape {
     static constexpr int PD = 2 * CW;                        // dwords per packed pixel
@@ -86,32 +87,40 @@ struct StreamShape {
     static constexpr int BUF = PB * PD;                      // dwords per batch buffer
 };
 
-// Columns whose partial sums a wavefront may keep in LDS between two passes over K.
-constexpr int kPassCols = 64;
-
 // What happens to the finished sums: EPI_PLAIN writes int32 (and/or scaled fp32) NHWC outputs;
 // EPI_CHAIN applies the fused layer epilogue and writes the next layer's packed input.
 enum : int { EPI_PLAIN = 0, EPI_CHAIN = 1 };
 
+// When the weights of 64 channels do not fit the registers of one wavefront (3x3 filters over 512
+// channels: 144 word pairs per lane), KH = CWT / CW wavefronts share a (row block, range): each keeps
+// CW of the CWT channel words of every tap and sums over its part of K; at the end of every group the
+// partial sums of the wavefronts 1 .. KH-1 go through LDS to wavefront 0, which runs the epilogue.
 template <int OP, int R, int CW, int CWT, int ST, int U, int EPI>
-__global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) {
+__global__ __launch_bounds__(256 * (CWT / CW)) void stream_conv_kernel(const StreamParams p) {
     typedef StreamShape<R, CW, ST, U> Sh;
     constexpr int TAPS = R * R, PD = Sh::PD, SP = Sh::SP, PB = Sh::PB, CH = Sh::CH, NBATCH = Sh::NBATCH;
-    constexpr int NPASS = CWT / CW;
-    static_assert(CWT % CW == 0, "passes must tile the channel words");
-    // Partial sums between passes (only when K does not fit the register file in one pass):
-    // [wave][column of the range][lane], private to the wavefront, so no barrier is needed.
-    extern __shared__ int32_t pass_partials[];
+    constexpr int KH = CWT / CW;
+    static_assert(CWT % CW == 0, "the wavefronts of a row block split the channel words evenly");
+    // hand-over of partial sums (KH > 1 only): [row block of the workgroup][group parity][pixel][lane]
+    extern __shared__ int32_t handover[];
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kh = KH > 1 ? wave_in_block % KH : 0;   // this wavefront's part of K
+    const int mbl = wave_in_block / KH;               // row block inside the workgroup
     // One-dimensional grid: workgroup = (range of groups, set of row blocks), the row-block set
-    // varying fastest, so that in dispatch order the ranges come one after the other; wave = row
-    // block inside the set.
-    const int wpb = blockDim.x >> 6;
-    const int nsets = ((p.M + 63) / 64 + wpb - 1) / wpb;
+    // varying fastest, so that in dispatch order the ranges come one after the other.
+    const int wpb = (blockDim.x >> 6) / KH;           // row blocks per workgroup
+    const int mblocks = (p.M + 63) / 64;
+    const int nsets = (mblocks + wpb - 1) / wpb;
     const int range = blockIdx.x / nsets;
-    const int mb = (blockIdx.x - range * nsets) * wpb + wave_in_block;
-    if (mb * 64 >= p.M) return;
+    int mb = (blockIdx.x - range * nsets) * wpb + mbl;
+    if (KH == 1) {
+        if (mb >= mblocks) return;
+    } else if (mb >= mblocks) {
+        // every wavefront of the workgroup must reach the barriers: a surplus wavefront repeats
+        // the last row block (and stores the same values a second time)
+        mb = mblocks - 1;
+    }
     // Lanes past the last output channel (M not a multiple of 64) take the last channel's
     // constants and output slot: they compute and store a duplicate of that channel, which
     // saves every per-lane mask in the epilogues; only the quantizer ballots drop their bits.
@@ -120,7 +129,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     const int m = m_ok ? m_real : p.M - 1;
     const uint64_t ok_mask = __ballot(m_ok);
 
-    plane2 w[TAPS][CW];   // weights of this lane's output channel for the current pass
+    plane2 w[TAPS][CW];   // this wavefront's weights of the lane's output channel
     const plane2* wsrc = p.Wi + ((int64_t)mb * p.Kw) * 64 + (m - mb * 64);   // duplicates read the last channel's weights
     // The row constant is loaded here but multiplied only in the epilogue: arithmetic on it in
     // the prologue would make every wavefront wait out a memory round trip before it even
@@ -197,8 +206,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     const int step_ho = (nranges / wgroups) % p.Ho;
     const int step_img = (nranges / wgroups) / p.Ho;
 
-    int32_t* const my_partials = pass_partials + (size_t)wave_in_block * kPassCols * 64 + lane;
-    sbytes_t xbase = (sbytes_t)(uintptr_t)p.A;
+    const sbytes_t xbase = (sbytes_t)(uintptr_t)p.A + (uint32_t)kh * (CW * 8u);
 
     // batch i of a group = pixels [c*PB, c*PB+np) of the strip of filter row r
     auto issue = [&](auto i_tag, uint32_t at, uint32_t* dst) {
@@ -243,7 +251,6 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
     };
 
     uint32_t buf[2][Sh::BUF];
-    int pass = 0;
     const uint32_t lane_out = (uint32_t)m;   // this lane's channel inside an output pixel
     const uint32_t lane_byte = lane_out * 4u;
     // raw buffer resources over the two outputs (the host guarantees they are below 4 GiB)
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         // A wavefront lowers its own priority as it nears its end: the ones behind catch up and all
         // finish together.
         {
-            const int left = (NPASS - 1 - pass) * count + (count - gi);   // groups still to do, this one included
+            const int left = count - gi;   // groups still to do, this one included
             if (left >= 4) __builtin_amdgcn_s_setprio(3);
             else if (left == 3) __builtin_amdgcn_s_setprio(2);
             else if (left == 2) __builtin_amdgcn_s_setprio(1);
@@ -315,8 +322,6 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
                 }
             }
         }
-        const int col_local = gi * U;
-        const bool last_pass = NPASS == 1 || pass + 1 == NPASS;
         // The skip values of the group are requested now and used after the K loop, where the
         // registers allow it; with eight resident channel words and seven accumulators they are
         // requested in the epilogue.
@@ -332,13 +337,10 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
             }
         };
         if constexpr (EPI == EPI_CHAIN && kSkipEarly) {
-            if (last_pass) load_skips();
+            if (kh == 0) load_skips();
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            acc[u] = 0;
-            if (NPASS > 1 && pass > 0) acc[u] = my_partials[(col_local + u) * 64];
-        }
+        for (int u = 0; u < U; ++u) acc[u] = 0;
         auto step = [&](auto i_tag) {
             constexpr int i = decltype(i_tag)::value;
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
@@ -354,10 +356,20 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         [&]<int... I>(std::integer_sequence<int, I...>) { (step(std::integral_constant<int, I>{}), ...); }
         (std::make_integer_sequence<int, NBATCH>{});
         goff = goff_next;
-        if (!last_pass) {
+        if constexpr (KH > 1) {
+            // Two slots per row block, alternating with the group: the barrier of group g+1 lies between
+            // wavefront 0 reading slot (g & 1) and the others writing it again for group g+2.
+            int32_t* const slot = handover + ((size_t)(mbl * 2 + (gi & 1)) * (KH - 1) * U) * 64 + lane;
+            if (kh > 0) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) my_partials[(col_local + u) * 64] = acc[u];
-            return;
+                for (int u = 0; u < U; ++u) slot[((kh - 1) * U + u) * 64] = acc[u];
+            }
+            __syncthreads();
+            if (kh > 0) return;
+#pragma unroll
+            for (int h = 0; h < KH - 1; ++h)
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] += slot[(h * U + u) * 64];
         }
         asm volatile("" : "+v"(rc_raw));   // keeps the multiply below out of the prologue
         const int32_t rc = p.cmul * rc_raw;
@@ -433,28 +445,25 @@ __global__ __launch_bounds__(256) void stream_conv_kernel(const StreamParams p) 
         }
     };
 
-    for (pass = 0; pass < NPASS; ++pass) {
-        // this pass's slice of the channel words: weights into registers, activations by offset
+    // this wavefront's channel words of every tap: weights into registers, activations by offset (xbase)
 #pragma unroll
-        for (int t = 0; t < TAPS; ++t)
+    for (int t = 0; t < TAPS; ++t)
 #pragma unroll
-            for (int c = 0; c < CW; ++c) w[t][c] = wsrc[(int64_t)(t * CWT + pass * CW + c) * 64];
-        xbase = (sbytes_t)(uintptr_t)p.A + (uint32_t)pass * (CW * 8u);
-        seek();
-        issue(std::integral_constant<int, 0>{}, goff, buf[0]);
+        for (int c = 0; c < CW; ++c) w[t][c] = wsrc[(int64_t)(t * CWT + kh * CW + c) * 64];
+    seek();
+    issue(std::integral_constant<int, 0>{}, goff, buf[0]);
 
-        int gi = 0;
-        while (gi < count) {
-            run_group(std::integral_constant<int, 0>{}, gi);
-            ++gi;
-            if constexpr ((NBATCH & 1) != 0) {
-                // an odd number of batches leaves the prefetched batch in the other buffer
-                if (gi < count) {
-                    run_group(std::integral_constant<int, 1>{}, gi);
-                    ++gi;
-                } else {
-                    break;
-                }
+    int gi = 0;
+    while (gi < count) {
+        run_group(std::integral_constant<int, 0>{}, gi);
+        ++gi;
+        if constexpr ((NBATCH & 1) != 0) {
+            // an odd number of batches leaves the prefetched batch in the other buffer
+            if (gi < count) {
+                run_group(std::integral_constant<int, 1>{}, gi);
+                ++gi;
+            } else {
+                break;
             }
         }
     }
@@ -477,7 +486,7 @@ int resident_waves_per_simd(Kernel kernel, int wpb, size_t lds, int* cache) {
 // wavefronts are meant to be resident at once, the same number on every SIMD, and each
 // should see enough groups to amortise loading its weights.  FATNN_STREAM_WPS sets the
 // wavefronts per SIMD (for measurements).
-int plan_ranges(int64_t mblocks, int64_t ngroups, int occ, int64_t max_groups_per_range) {
+int plan_ranges(int64_t mblocks, int64_t ngroups, int occ) {
     // As many wavefronts per SIMD as stay resident, up to 6 (more only adds weight-load traffic at
     // the start); beyond four only while each still gets three pixel groups, and never more
     // wavefronts than groups.  (One or two wavefronts per SIMD issue the logic/popcount pairs at
@@ -492,8 +501,6 @@ int plan_ranges(int64_t mblocks, int64_t ngroups, int occ, int64_t max_groups_pe
     }
     int64_t ranges = (1024 * wps) / mblocks;
     if (ranges < 1) ranges = 1;
-    const int64_t need = (ngroups + max_groups_per_range - 1) / max_groups_per_range;
-    if (ranges < need) ranges = need;
     if (ranges > ngroups) ranges = ngroups;
     return (int)ranges;
 }
@@ -504,29 +511,30 @@ int launch_inst(StreamParams p, int64_t out_rows, int64_t Wo, hipStream_t stream
     p.tailU = (int32_t)(Wo - (int64_t)(p.wgroups - 1) * U);
     const int64_t ngroups = out_rows * p.wgroups;
     if (ngroups <= 0 || ngroups > 0x7FFFFFF0LL) return -2;
+    constexpr int KH = CWT / CW;                      // wavefronts per (row block, range)
     const int mblocks = (p.M + 63) / 64;
-    const int wpb = mblocks < 4 ? mblocks : 4;
-    const size_t lds = (CWT > CW) ? (size_t)wpb * kPassCols * 64 * sizeof(int32_t) : 0;
-    const int64_t max_groups = (CWT > CW) ? kPassCols / U : 0x7FFFFFFF;
+    const int wpb = mblocks < 4 ? mblocks : 4;        // row blocks per workgroup
+    const int waves = wpb * KH;
+    const size_t lds = KH > 1 ? (size_t)wpb * 2 * (KH - 1) * U * 64 * sizeof(int32_t) : 0;
     auto launch = [&](auto kernel, int* cache) {
-        const int occ = resident_waves_per_simd(kernel, wpb, lds, cache);
-        const int ranges = plan_ranges(mblocks, ngroups, occ, max_groups);
+        const int occ = resident_waves_per_simd(kernel, waves, lds, cache);
+        const int ranges = plan_ranges((int64_t)mblocks * KH, ngroups, occ);
         p.gq = (int32_t)(ngroups / ranges);
         p.gr = (int32_t)(ngroups % ranges);
         dim3 grid((unsigned)(ranges * ((mblocks + wpb - 1) / wpb)));
         const LaunchTiming t = take_launch_timing();
-        hipExtLaunchKernelGGL(kernel, grid, dim3(64 * wpb), lds, stream, t.start, t.stop, 0, p);
+        hipExtLaunchKernelGGL(kernel, grid, dim3(64 * waves), lds, stream, t.start, t.stop, 0, p);
         return hipGetLastError() == hipSuccess ? 0 : -1;
     };
     if (p.Xn != nullptr) {
         if constexpr (OP == OP_TERNARY) {
-            static int cache[5] = {0, 0, 0, 0, 0};
+            static int cache[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
             return launch(stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_CHAIN>, cache);
         } else {
             return -3;
         }
     }
-    static int cache[5] = {0, 0, 0, 0, 0};
+    static int cache[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     return launch(stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_PLAIN>, cache);
 }
 
@@ -535,7 +543,7 @@ constexpr int group_u(int R, int CW, int ST) {
     if (R == 3) return (ST == 1) ? (CW == 2 ? 8 : 4) : (CW >= 8 ? 2 : 4);
     return (CW >= 8) ? 4 : (CW == 4 ? 4 : 8);   // 1x1
 }
-// Channel words kept in registers per pass: everything, except for 3x3 filters over 512 channels.
+// Channel words one wavefront keeps in registers: all of them, except for 3x3 filters over 512 channels.
 constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : CWT; }
 
 // Second group size of a shape (0 = none).  ResNet's rows are 56, 28, 14 and 7 pixels wide: groups of
