@@ -316,6 +316,22 @@ def test_conv_bordered_input_on_the_tiled_kernel(monkeypatch, Cin, Cout, H, W, R
     assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, mode))
 
 
+@pytest.mark.parametrize("Cout", [1, 64, 65, 256, 300, 512, 530])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_conv_512_channels_wavefront_pairs(Cout, stride):
+    """3x3 over 512 channels: two wavefronts per row block split K and meet in LDS once per group; the number of
+    row blocks decides how many wavefronts of a workgroup are surplus."""
+    rnd = np.random.default_rng(Cout + stride)
+    Lw = rnd.integers(0, 3, size=(Cout, 3, 3, 512), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(3, 9, 11, 512), dtype=np.int8)
+    scale = rnd.uniform(0.5, 1.5, Cout).astype(np.float32)
+    for mode in (0, 1):
+        Y, Yf = conv_gpu(Lw, Lx, stride, 1, mode, bordered=True, scale=dev(scale))
+        want = oracle.ternary_conv2d(Lw, Lx, stride, 1, mode)
+        assert np.array_equal(Y.cpu().numpy(), want)
+        assert np.array_equal(Yf.cpu().numpy(), oracle.scale_epilogue(want, scale, None, False))
+
+
 def test_bordered_pack_layout():
     rnd = np.random.default_rng(77)
     B, H, W, C = 2, 5, 4, 64
@@ -450,7 +466,8 @@ def test_twobit_on_ternary_data_equals_ternary_path():
     assert np.array_equal(C2.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
 
 
-@pytest.mark.parametrize("R,stride,pad,Cin", [(3, 1, 1, 64), (3, 2, 1, 64), (1, 1, 0, 64), (3, 1, 1, 96), (3, 1, 1, 256)])
+@pytest.mark.parametrize("R,stride,pad,Cin", [(3, 1, 1, 64), (3, 2, 1, 64), (1, 1, 0, 64), (3, 1, 1, 96), (3, 1, 1, 256),
+                                              (3, 1, 1, 512), (3, 2, 1, 512), (1, 1, 0, 512)])
 def test_twobit_conv_parity(R, stride, pad, Cin):
     rnd = np.random.default_rng(R + stride + Cin)
     Lw = rnd.integers(0, 3, size=(70, R, R, Cin), dtype=np.int8)
