@@ -92,7 +92,7 @@ struct StreamShape {
 enum : int { EPI_PLAIN = 0, EPI_CHAIN = 1 };
 
 // When the weights of 64 channels do not fit the registers of one wavefront (3x3 filters over 512
-// channels: 144 word pairs per lane), KH = CWT / CW wavefronts share a (row block, range): each keeps
+// channels: 144 word pairs per lane) or fill them (256 channels), KH = CWT / CW wavefronts share a (row block, range): each keeps
 // CW of the CWT channel words of every tap and sums over its part of K; at the end of every group the
 // partial sums of the wavefronts 1 .. KH-1 go through LDS to wavefront 0, which runs the epilogue.
 template <int OP, int R, int CW, int CWT, int ST, int U, int EPI>
@@ -214,7 +214,13 @@ __global__ __launch_bounds__(256 * (CWT / CW)) void stream_conv_kernel(const Str
         constexpr int r = i / CH, c = i % CH;
         constexpr int np = (SP - c * PB) < PB ? (SP - c * PB) : PB;
         const sptr_t src = (sptr_t)(xbase + (at + (uint32_t)r * row_bytes + (uint32_t)(c * PB) * kPixBytes));
-        sload_run<np * PD>(src, dst);
+        if constexpr (KH == 1) {
+            sload_run<np * PD>(src, dst);   // the pixels of a batch are contiguous
+        } else {
+            // this wavefront's CW channel words of each pixel, CWT word pairs apart
+#pragma unroll
+            for (int j = 0; j < np; ++j) sload_run<PD>(src + j * (2 * CWT), dst + j * PD);
+        }
     };
 
     int32_t acc[U];
@@ -543,8 +549,11 @@ constexpr int group_u(int R, int CW, int ST) {
     if (R == 3) return (ST == 1) ? (CW == 2 ? 8 : 4) : (CW >= 8 ? 2 : 4);
     return (CW >= 8) ? 4 : (CW == 4 ? 4 : 8);   // 1x1
 }
-// Channel words one wavefront keeps in registers: all of them, except for 3x3 filters over 512 channels.
-constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : CWT; }
+// Channel words one wavefront keeps in registers.  3x3 filters over 512 channels do not fit one wavefront
+// (two share a row block, eight channel words each); over 256 channels they would fit, but two wavefronts
+// with four channel words each leave room for four or five wavefronts per SIMD instead of three and
+// measured 10 % faster.
+constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT > 8) ? 8 : ((R == 3 && CWT == 8) ? 4 : CWT); }
 
 // Second group size of a shape (0 = none).  ResNet's rows are 56, 28, 14 and 7 pixels wide: groups of
 // seven leave no partly empty group at the end of a row.  (For 64-channel layers groups of fourteen
