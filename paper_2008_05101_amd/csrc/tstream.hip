@@ -553,7 +553,15 @@ constexpr int group_u(int R, int CW, int ST) {
 // over 256 channels they would, at three wavefronts per SIMD.  Both are split into wavefronts of four
 // channel words (two per row block for 256 channels, four for 512), which leaves room for four or five
 // wavefronts per SIMD: measured 10 % faster for 256 channels, and 6 % faster than eight-word pairs for 512.
-constexpr int resident_cw(int R, int CWT) { return (R == 3 && CWT >= 8) ? 4 : CWT; }
+constexpr int resident_cw(int R, int CWT, int ST, int U) {
+    if (R != 3) return CWT;
+    if (CWT >= 8) return 4;
+    // 128 channels: pairs of two-word wavefronts pay with the large groups and on the stride-2 layer
+    // (chained trunk at batch 64: 31 -> 29.5 us, 20.9 -> 18.9 us); with groups of four at stride 1 (the
+    // batch-32 layer of the default benchmark) the single four-word wavefront is faster, 17.9 against 19.3 us
+    if (CWT == 4 && (U == 7 || ST == 2)) return 2;
+    return CWT;
+}
 
 // Second group size of a shape (0 = none).  ResNet's rows are 56, 28, 14 and 7 pixels wide: groups of
 // seven leave no partly empty group at the end of a row.  (For 64-channel layers groups of fourteen
@@ -594,10 +602,11 @@ int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride,
 #define FATNN_STREAM_CASE(RR, CC, SS)                                                                          \
     if (R == RR && Cw == CC && stride == SS) {                                                                 \
         constexpr int UU = group_u(RR, CC, SS);                                                                \
-        constexpr int RC = resident_cw(RR, CC);                                                                \
+        constexpr int RC = resident_cw(RR, CC, SS, UU);                                                        \
         if constexpr (alt_u(RR, CC, SS) != 0) {                                                                \
-            if (U == alt_u(RR, CC, SS))                                                                        \
-                return launch_inst<OP_TERNARY, RR, RC, CC, SS, alt_u(RR, CC, SS)>(p, out_rows, Wo, stream);    \
+            constexpr int UA = alt_u(RR, CC, SS);                                                              \
+            if (U == UA)                                                                                       \
+                return launch_inst<OP_TERNARY, RR, resident_cw(RR, CC, SS, UA), CC, SS, UA>(p, out_rows, Wo, stream); \
         }                                                                                                      \
         if (op == OP_TERNARY) return launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);    \
         if (op == OP_XOR_PAIR) return launch_inst<OP_XOR_PAIR, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);  \
