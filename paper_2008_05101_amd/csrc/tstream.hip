@@ -556,9 +556,9 @@ constexpr int group_u(int R, int CW, int ST) {
 constexpr int resident_cw(int R, int CWT, int ST, int U) {
     if (R != 3) return CWT;
     if (CWT >= 8) return 4;
-    // 128 channels: pairs of two-word wavefronts pay with the large groups and on the stride-2 layer
-    // (chained trunk at batch 64: 31 -> 29.5 us, 20.9 -> 18.9 us); with groups of four at stride 1 (the
-    // batch-32 layer of the default benchmark) the single four-word wavefront is faster, 17.9 against 19.3 us
+    // 128 channels: pairs of two-word wavefronts pay with the seven-pixel groups and on the stride-2 layer
+    // (chained trunk at batch 64: 31 -> 29.5 us, 20.9 -> 18.9 us); with groups of four at stride 1 (rows
+    // that are no multiple of seven) the single four-word wavefront is faster, 17.9 against 19.3 us
     if (CWT == 4 && (U == 7 || ST == 2)) return 2;
     return CWT;
 }
@@ -575,12 +575,13 @@ constexpr int alt_u(int R, int CW, int ST) {
 // =2 uses it wherever a kernel exists (for tests of those kernels on small inputs).
 int pick_group_size(int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo, int64_t mblocks) {
     const int alt = alt_u(R, Cw, stride);
-    if (op == OP_TERNARY && alt != 0 && Wo % alt == 0) {
+    if (alt != 0 && Wo % alt == 0) {
         const char* e = getenv("FATNN_STREAM_U7");
         const char mode = e == nullptr ? '1' : e[0];
-        // by default only where the larger groups still leave every SIMD three of them with eight resident
-        // channel words (measured down to 3.5 per SIMD: 512 channels at 7x7, batch 64) and twelve otherwise
-        const int64_t enough = 1024 * (Cw <= 4 ? 12 : 3);
+        // 128 channels: always (with the two-word wavefront pairs that go with it, measured 15-20 % faster
+        // from batch 2 to 32 at 28x28 and equal beyond); 256 and 512 channels: only where the larger groups
+        // still leave every SIMD three of them (measured: slower at 1-2 per SIMD, faster from 3.5)
+        const int64_t enough = Cw <= 4 ? 0 : 3 * 1024;
         if (mode == '2' || (mode != '0' && out_rows * (Wo / alt) * mblocks >= enough)) return alt;
     }
     return group_u(R, Cw, stride);
@@ -605,8 +606,12 @@ int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride,
         constexpr int RC = resident_cw(RR, CC, SS, UU);                                                        \
         if constexpr (alt_u(RR, CC, SS) != 0) {                                                                \
             constexpr int UA = alt_u(RR, CC, SS);                                                              \
-            if (U == UA)                                                                                       \
-                return launch_inst<OP_TERNARY, RR, resident_cw(RR, CC, SS, UA), CC, SS, UA>(p, out_rows, Wo, stream); \
+            constexpr int RA = resident_cw(RR, CC, SS, UA);                                                    \
+            if (U == UA) {                                                                                     \
+                if (op == OP_TERNARY) return launch_inst<OP_TERNARY, RR, RA, CC, SS, UA>(p, out_rows, Wo, stream);   \
+                if (op == OP_XOR_PAIR) return launch_inst<OP_XOR_PAIR, RR, RA, CC, SS, UA>(p, out_rows, Wo, stream); \
+                return launch_inst<OP_TWOBIT_TERNARY, RR, RA, CC, SS, UA>(p, out_rows, Wo, stream);            \
+            }                                                                                                  \
         }                                                                                                      \
         if (op == OP_TERNARY) return launch_inst<OP_TERNARY, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);    \
         if (op == OP_XOR_PAIR) return launch_inst<OP_XOR_PAIR, RR, RC, CC, SS, UU>(p, out_rows, Wo, stream);  \
