@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by the same counters' readings for a plain copy of known size (profiles/*.md give the
 # commands, the raw readings and the scale factors 2.000 / 1.000).
-MEASURED_TRAFFIC_BYTES = {"cfg2": int((3099.6 * 2.000 + 25088.0 * 1.000) * 1024),
+MEASURED_TRAFFIC_BYTES = {"cfg2": int((2591.6 * 2.000 + 25088.0 * 1.000) * 1024),
                           "cfg4": int((179007.2 * 2.000 + 262144.0 * 1.000) * 1024)}
 
 
