@@ -2,11 +2,11 @@
 //
 // Convolution layers of CNNs have few output channels (64..512), a short K per
 // output (R*S*Cin <= a few thousand) and very many columns (batch x pixels).  Here
-// a wavefront keeps the packed weights of 64 output channels in VGPRs for its whole
-// life (lane = output channel) and walks over a contiguous range of groups of U
-// neighbouring output pixels.  The activation plane words of a pixel are the same
-// for every lane, so they are fetched with scalar loads into SGPRs and enter the
-// three-input logic instruction as its scalar operand: no LDS, no barrier, and the
+// a wavefront keeps packed weights of 64 output channels in VGPRs for its whole
+// life (lane = output channel) and walks over groups of U neighbouring output
+// pixels.  The activation plane words of a pixel are the same for every lane, so
+// they are fetched with scalar loads into SGPRs and enter the three-input logic
+// instruction as its scalar operand: no LDS and no barrier in the K loop, and the
 // work of a wavefront can be any number of groups, which removes the tile
 // quantisation that small layers suffer on 256 CUs.
 //
@@ -16,6 +16,18 @@
 // group that touch it: an image-row strip of (U-1)*stride + R input pixels serves
 // U output pixels.  The input must be the bordered layout (physical ring of
 // value-0 pixels, slack behind the last image), so strips never need a bounds check.
+//
+// What was measured on the chip and shaped the rest (details at the places):
+//  * a wavefront holds at most four channel words of every tap; wider layers are
+//    split over two or four wavefronts per block of 64 channels that meet in LDS
+//    once per group (more wavefronts per SIMD beat fewer, larger ones);
+//  * wavefronts lower their own priority towards their end, so the wavefronts of a
+//    SIMD finish together instead of one after the other;
+//  * the ranges that get one group more are the first in dispatch order, which
+//    spreads them over the SIMDs; for the write-heavy shapes a wavefront takes
+//    every n-th group, so that the output is written as one compact front;
+//  * outputs are stored through buffer resources (no vector address arithmetic)
+//    with device scope + non-temporal policy.
 //
 // The arithmetic is the reduced form of Eq. 3 (Section 3.3): 2 logic + 2 popcount
 // instructions per 32 elements; the two-bit form of Eq. 2 needs 4 + 4.
@@ -91,10 +103,9 @@ struct StreamShape {
 // EPI_CHAIN applies the fused layer epilogue and writes the next layer's packed input.
 enum : int { EPI_PLAIN = 0, EPI_CHAIN = 1 };
 
-// When the weights of 64 channels do not fit the registers of one wavefront (3x3 filters over 512
-// channels: 144 word pairs per lane) or fill them (256 channels), KH = CWT / CW wavefronts share a (row block, range): each keeps
-// CW of the CWT channel words of every tap and sums over its part of K; at the end of every group the
-// partial sums of the wavefronts 1 .. KH-1 go through LDS to wavefront 0, which runs the epilogue.
+// KH = CWT / CW wavefronts share a (row block, range) when one wavefront does not hold all channel words:
+// each keeps CW of the CWT channel words of every tap and sums over its part of K; at the end of every
+// group the partial sums of the wavefronts 1 .. KH-1 go through LDS to wavefront 0, which runs the epilogue.
 template <int OP, int R, int CW, int CWT, int ST, int U, int EPI>
 __global__ __launch_bounds__(256 * (CWT / CW)) void stream_conv_kernel(const StreamParams p) {
     typedef StreamShape<R, CW, ST, U> Sh;
