@@ -117,6 +117,12 @@ def test_chain_epilogue_nan_and_inf_in_the_skip(relu, out_mode):
     assert np.array_equal(interior, lv_want)
 
 
+@pytest.mark.parametrize("Cin,Cout,H,W,use_skip", [(128, 256, 9, 14, True), (256, 512, 6, 14, False)])
+def test_chain_epilogue_stride2_groups_of_seven(monkeypatch, Cin, Cout, H, W, use_skip):
+    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+    test_chain_epilogue_exact(Cin, Cout, H, W, 3, 2, 1, 1, 1, 1, use_skip, True)
+
+
 def test_two_layers_chained_equal_the_oracle_pipeline():
     rnd = np.random.default_rng(99)
     B, H, W = 4, 14, 14

@@ -316,6 +316,18 @@ def test_conv_bordered_input_on_the_tiled_kernel(monkeypatch, Cin, Cout, H, W, R
     assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, stride, pad, mode))
 
 
+@pytest.mark.parametrize("Cin,Cout,H,W", [(128, 256, 9, 14), (128, 70, 14, 28), (256, 512, 6, 14), (256, 130, 14, 13)])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_conv_stride2_groups_of_seven(monkeypatch, Cin, Cout, H, W, mode):
+    """Stride-2 3x3 layers with seven-pixel groups (output rows of 7: W = 13 or 14; 14: W = 28), forced on small inputs."""
+    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+    rnd = np.random.default_rng(Cin + Cout + H + W + mode)
+    Lw = rnd.integers(0, 3, size=(Cout, 3, 3, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(4, H, W, Cin), dtype=np.int8)
+    Y, _ = conv_gpu(Lw, Lx, 2, 1, mode, bordered=True)
+    assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, 2, 1, mode))
+
+
 @pytest.mark.parametrize("Cout", [1, 64, 65, 256, 300, 512, 530])
 @pytest.mark.parametrize("stride", [1, 2])
 def test_conv_512_channels_wavefront_pairs(Cout, stride):
