@@ -1,9 +1,11 @@
-// Ternary GEMM with very few columns (N <= 8): matrix-vector shaped, bound by streaming
-// the packed weights once.  A wavefront owns RW weight rows; its 64 lanes split K (lane l
-// takes k-words l, l+64, ...), so every load of a weight row is one contiguous 512-byte
-// request.  Per k-word the lane evaluates the same reduced form of Eq. 3 as the tiled
-// kernel (2 logic + 2 popcount instructions per word pair and column); a butterfly over
-// the lanes then sums the partial popcounts.
+// Ternary GEMM with few columns (fully connected layers at small batch; the paper treats them as
+// convolutions whose kernel covers the whole feature map, Supplementary S1): matrix-vector shaped,
+// bound by streaming the packed weights.  A wavefront owns RW weight rows; its 64 lanes split K
+// (lane l takes k-words l, l+64, ...), so every load of a weight row is one contiguous 512-byte
+// request.  Per k-word the lane evaluates the same reduced form of Eq. 3 as the tiled kernel
+// (2 logic + 2 popcount instructions per word pair and column); a butterfly over the lanes then
+// sums the partial popcounts.  More than NC columns are done NC at a time; the wavefront's weight
+// rows (a few KB) come from L1 again for every chunk.
 #include "fatnn_device.h"
 
 namespace fatnn {
@@ -22,6 +24,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const GemmParams p) {
     const int m0 = wave * RW;
     if (m0 >= p.M) return;
 
+  for (int n0 = 0; n0 < p.N; n0 += NC) {
     int32_t acc[RW][NC];
 #pragma unroll
     for (int r = 0; r < RW; ++r)
@@ -34,7 +37,7 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const GemmParams p) {
         for (int c = 0; c < NC; ++c) {
             a[c].x = 0u;
             a[c].y = 0u;
-            if (c < p.N) a[c] = p.A[(int64_t)c * p.Kw + kw];
+            if (n0 + c < p.N) a[c] = p.A[(int64_t)(n0 + c) * p.Kw + kw];
         }
 #pragma unroll
         for (int r = 0; r < RW; ++r) {
@@ -69,21 +72,31 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const GemmParams p) {
             for (int cc = 0; cc < NC; ++cc)
                 if (rr == r && cc == c) sum = acc[rr][cc];
         const int m = m0 + r;
-        if (m < p.M && c < p.N) {
+        const int n = n0 + c;
+        if (m < p.M && n < p.N) {
             const int32_t v = p.cmul * p.rowc[m] - sum;
-            if (p.C != nullptr) p.C[(int64_t)m * p.ldc_m + (int64_t)c * p.ldc_n] = v;
+            if (p.C != nullptr) p.C[(int64_t)m * p.ldc_m + (int64_t)n * p.ldc_n] = v;
             if (p.Cf != nullptr) {
                 float f = p.scale[m] * (float)v;
                 if (p.bias != nullptr) f = f + p.bias[m];
-                p.Cf[(int64_t)m * p.ldf_m + (int64_t)c * p.ldf_n] = f;
+                p.Cf[(int64_t)m * p.ldf_m + (int64_t)n * p.ldf_n] = f;
             }
         }
     }
+  }
 }
 
 }  // namespace
 
-bool skinny_supported(const GemmParams& p, int op) { return op == OP_TERNARY && !p.is_conv && p.N <= 8; }
+// N <= 8 always; up to 16 columns (two chunks) for a long K while the tiled kernel would have fewer
+// workgroup tiles than compute units.  Measured for M = 4096, K = 4608: the tiled kernel takes 24-26 us for
+// any N <= 128 (a latency-bound K loop on 64 workgroups), this kernel 13 us at N = 16, but 24.5 us at
+// N = 32 and 46 us at N = 64, and with a short K most of its lanes idle.
+bool skinny_supported(const GemmParams& p, int op) {
+    if (op != OP_TERNARY || p.is_conv) return false;
+    if (p.N <= 8) return true;
+    return p.N <= 16 && p.Kw >= 128 && (int64_t)((p.M + 63) / 64) < 256;
+}
 
 int launch_skinny_gemm(const GemmParams& p, hipStream_t stream) {
     const int waves = (p.M + RW - 1) / RW;
