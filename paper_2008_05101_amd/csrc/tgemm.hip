@@ -114,15 +114,10 @@ __device__ __forceinline__ int32_t finalize<OP_TWOBIT_UNIFORM>(const Acc<OP_TWOB
     return 9 * p.K - 2 * acc.s00 - 4 * acc.s01 - 8 * acc.s11;
 }
 
-// KS > 1: KS sets of WM x WN wavefronts share one output tile and split the k-words of every
-// stage between them (set s takes k-words s, s + KS, ...); the partial sums meet in LDS at the
-// end.  For problems with fewer tiles than SIMDs it multiplies the wavefronts in flight.
-template <int OP, int WM, int WN, int TM, int TN, bool CONV, int KS = 1>
-__global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
+template <int OP, int WM, int WN, int TM, int TN, bool CONV>
+__global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
                                                                         const int ntiles) {
-    constexpr int NT = 64 * WM * WN * KS;
-    static_assert(KT % KS == 0, "the sets split a stage evenly");
-    static_assert(KS == 1 || OP != OP_TWOBIT_UNIFORM, "the LDS reduction handles one accumulator per output");
+    constexpr int NT = 64 * WM * WN;
     constexpr int BM = WM * 8 * TM;
     constexpr int BN = WN * 8 * TN;
     constexpr int LW = (BM * KT) / NT;   // staged word pairs per thread, weights
@@ -158,10 +153,8 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int ks = KS == 1 ? 0 : wave / (WM * WN);   // k-split set of this wavefront
-    const int wave_in_set = wave - ks * (WM * WN);
-    const int wave_m = wave_in_set % WM;
-    const int wave_n = wave_in_set / WM;
+    const int wave_m = wave % WM;
+    const int wave_n = wave / WM;
     const int ly = lane >> 3;
     const int lx = lane & 7;
 
@@ -304,17 +297,16 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const 
             // the per-word test is a scalar branch
             const int jn = p.Kw - kt * KT;
             plane2 w[2][TM], a[2][TN];
-            read_frag(buf, ks, w[0], a[0]);
+            read_frag(buf, 0, w[0], a[0]);
 #pragma unroll
-            for (int jj = 0; jj < KT / KS; ++jj) {
-                const int j = jj * KS + ks;   // this set's k-word of the stage
+            for (int j = 0; j < KT; ++j) {
                 if (j >= jn) break;
-                if (jj + 1 < KT / KS && j + KS < jn) read_frag(buf, j + KS, w[(jj + 1) & 1], a[(jj + 1) & 1]);
+                if (j + 1 < KT && j + 1 < jn) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
                 FATNN_VOP3_RUN_PHASE();
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[jj & 1][i], a[jj & 1][c]);
+                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -347,27 +339,6 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const 
             if (kt + 2 < nkt) stage(0, set0);
             __syncthreads();
         }
-    }
-
-    if constexpr (KS > 1) {
-        // partial sums of the sets 1 .. KS-1 go through LDS to set 0 ([set][accumulator][thread of the set])
-        constexpr int SET = 64 * WM * WN;
-        __shared__ int32_t partial[(KS - 1) * TM * TN * SET];
-        const int t = wave_in_set * 64 + lane;
-        if (ks > 0) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int c = 0; c < TN; ++c) partial[((ks - 1) * TM * TN + i * TN + c) * SET + t] = acc[i][c].v;
-        }
-        __syncthreads();
-        if (ks > 0) return;
-#pragma unroll
-        for (int s2 = 0; s2 < KS - 1; ++s2)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int c = 0; c < TN; ++c) acc[i][c].v += partial[(s2 * TM * TN + i * TN + c) * SET + t];
     }
 
     // ---- epilogue: Eq. 3's subtraction, then the optional fp32 scale -----------------------
@@ -426,7 +397,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS, 2) void plane_gemm_kernel(const 
     }
 }
 
-template <int OP, int WM, int WN, int TM, int TN, int KS = 1>
+template <int OP, int WM, int WN, int TM, int TN>
 int launch_shape(const GemmParams& p, hipStream_t stream) {
     constexpr int BM = WM * 8 * TM;
     constexpr int BN = WN * 8 * TN;
@@ -437,29 +408,28 @@ int launch_shape(const GemmParams& p, hipStream_t stream) {
     const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
     const LaunchTiming t = take_launch_timing();
     if (p.is_conv)
-        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true, KS>), dim3(grid), dim3(64 * WM * WN * KS), 0,
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true>), dim3(grid), dim3(64 * WM * WN), 0,
                               stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
     else
-        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false, KS>), dim3(grid), dim3(64 * WM * WN * KS), 0,
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false>), dim3(grid), dim3(64 * WM * WN), 0,
                               stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// Picks the workgroup shape.  Measured on this chip, the 64 x 64 workgroup tile (four wavefronts
-// of 32 x 32, 4 x 4 accumulators per lane, six wavefronts per SIMD) matches the 128 x 128 tile
-// (8 x 8 accumulators, three per SIMD) up to 8192^3 and beats every larger shape below about
-// 16 K wavefront tiles of 64 x 64, where tile quantisation over 256 CUs matters; the large tile
-// keeps a few per cent on very large problems with a shallow K (fewer operand re-reads).
+// Picks the workgroup shape, all 2 x 2 wavefronts.  Measured on this chip: the 64 x 64 tile (4 x 4
+// accumulators per lane, six wavefronts per SIMD) matches the 128 x 128 tile (8 x 8 accumulators, three per
+// SIMD) up to 8192^3 and beats it below about 16 K wavefront tiles of 64 x 64, where tile quantisation
+// over 256 CUs matters; the large tile keeps a few per cent on very large problems with a shallow K
+// (fewer operand re-reads).  Below about a thousand such tiles the 32 x 32 tile (2 x 2 accumulators) puts
+// four times as many wavefronts to work and wins by up to 30 % (4096 x 64 x 4608: 25 -> 18 us,
+// 1536^2 x 4096: 53 -> 41 us); at 2048^2 the two are equal, at 3072^3 the 64 x 64 tile is 6 % faster.
 template <int OP, int TM, int TN>
 int launch_op(const GemmParams& p, hipStream_t stream) {
     constexpr int WTM = 8 * TM, WTN = 8 * TN;
     const int64_t wave_tiles = (((int64_t)p.M + WTM - 1) / WTM) * (((int64_t)p.N + WTN - 1) / WTN);
     if (wave_tiles >= 16 * 1024 && p.M > WTM) return launch_shape<OP, 2, 2, TM, TN>(p, stream);
-    // fewer than two wavefronts per SIMD and a long K: two sets of wavefronts per tile split K
-    if constexpr (OP != OP_TWOBIT_UNIFORM) {
-        if (wave_tiles * 4 < 2 * 1024 && p.Kw >= 64) return launch_shape<OP, 2, 2, TM / 2, TN / 2, 2>(p, stream);
-    }
-    return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
+    if (wave_tiles >= 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
+    return launch_shape<OP, 2, 2, 2, 2>(p, stream);
 }
 
 }  // namespace

@@ -130,8 +130,8 @@ def test_gemm_parity_small_and_ragged(M, N, K, mode):
 @pytest.mark.parametrize("M,N,K", [(2048, 2100, 96), (64, 70000, 64), (2100, 1100, 130), (4096, 8, 300),
                                    (8200, 8300, 40), (64, 1100000, 33)])
 def test_gemm_parity_every_workgroup_shape(M, N, K):
-    # from a few to more than 16 K tiles of 64x64: the 64x64 and the 128x128 workgroup shapes, and the
-    # one-row-block case that stays on the small shape however many tiles there are
+    # from a few to more than 16 K tiles of 64x64: the 32x32, 64x64 and 128x128 workgroup shapes, and the
+    # one-row-block case that stays on a small shape however many tiles there are
     rnd = np.random.default_rng(M + N + K)
     Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
     La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
@@ -141,8 +141,8 @@ def test_gemm_parity_every_workgroup_shape(M, N, K):
 
 @pytest.mark.parametrize("M,N,K", [(64, 64, 2048), (130, 70, 2100), (200, 300, 2049), (512, 700, 2304), (9, 1000, 4609)])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_gemm_parity_split_k_workgroups(M, N, K, mode):
-    # few tiles and a long K: two sets of wavefronts per tile split every K stage and reduce through LDS
+def test_gemm_parity_few_tiles_long_k(M, N, K, mode):
+    # few tiles and a long K (the 32x32 workgroup tile, many K stages)
     rnd = np.random.default_rng(M + 3 * N + K + mode)
     Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
     La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
