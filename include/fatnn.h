@@ -20,6 +20,16 @@
  *   - Inputs are LEVEL INDICES l in {0,1,2} (int8), l = popcount of the paper's
  *     codec.  Weights mean l-1 in {-1,0,+1}.  Activations mean l-1 (FATNN_SYM) or
  *     l in {0,1,2} (FATNN_RELU, the paper's second constraint in Section 3.3).
+ *   - Inputs outside that set break the paper's first constraint (Section 3.3).  The
+ *     packing calls run asynchronously and cannot return that fact; they ADD the
+ *     number of such elements to the device counter `n_invalid` and pack them as
+ *     the value 0.  FATNN_ERR_LEVEL is the status for "the counter came back
+ *     non-zero": fatnn_level_status(count) forms it, and the Python binding raises
+ *     it when called with check_levels=True (which reads the counter back, i.e.
+ *     synchronises).
+ *   - Apart from the two measurement hooks at the end (fatnn_set_tuning, process-wide
+ *     atomics; fatnn_time_next_launch, per thread) the library keeps no state, and
+ *     every call is re-entrant.
  *   - Zero-sized problems (no rows / no columns / no batch) succeed and launch
  *     nothing.  K (or Cin) must be at least 1.
  *
@@ -50,7 +60,7 @@ typedef enum {
     FATNN_OK = 0,
     FATNN_ERR_NULL = -1,        /* a required pointer is NULL                         */
     FATNN_ERR_SHAPE = -2,       /* negative / zero / inconsistent dimension           */
-    FATNN_ERR_LEVEL = -3,       /* reserved for callers that read back *n_invalid     */
+    FATNN_ERR_LEVEL = -3,       /* an input outside the paper's level set: see below  */
     FATNN_ERR_ALIGN = -4,       /* pointer not aligned as documented                  */
     FATNN_ERR_SIZE = -5,        /* buffer too small, or dimension beyond the limits   */
     FATNN_ERR_UNSUPPORTED = -6, /* valid but not implemented (never a wrong answer)   */
@@ -247,6 +257,22 @@ int fatnn_pack_binary(const int8_t *bits, int64_t rows, int64_t K, void *packed,
                       int32_t *n_invalid, void *stream);
 int fatnn_binary_gemm(const void *Wb, const void *Ab, int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
                       void *stream);
+
+/* FATNN_OK for a zero count of out-of-set inputs, FATNN_ERR_LEVEL otherwise (first constraint of
+ * Section 3.3).  `n_invalid_host` is the value of a packing call's counter copied to the host. */
+int fatnn_level_status(int64_t n_invalid_host);
+
+/*
+ * Measurement switches (no paper passage: they serve the kernel comparisons in the report).
+ * Process-wide, stored in atomics, read by every later launch; a negative argument keeps the
+ * current value.  Their initial values come from the environment variables FATNN_CONV_KERNEL
+ * (=tiled), FATNN_STREAM_WPS and FATNN_STREAM_U7, read once on first use.
+ *   conv_kernel         0 = automatic, 1 = convolutions always take the LDS-tiled kernel
+ *   stream_wps          wavefronts per SIMD of the column-streaming kernel, 0 = planned, at most 8
+ *   seven_pixel_groups  0 = off, 1 = by the size rule, 2 = wherever a kernel exists
+ * Results never depend on these, only the kernel and launch shape chosen.
+ */
+int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups);
 
 /*
  * Measurement hook (no paper passage: it serves the roofline report).  The next

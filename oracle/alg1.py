@@ -15,7 +15,7 @@ import numpy as np
 
 # Table 1: value -> codec.  The value 0 has two spellings.
 CODEC_OF_VALUE = {-1: (0b00,), 0: (0b01, 0b10), +1: (0b11,)}
-AUXI_FIELD = 0b01          # Section 3.3: "auxi ... a pre-defined constant in codec 2'b01"
+AUXI_FIELD = 0b01          # auxi of Section 3.3 (Eq. 5): the fixed field with codec 01
 AUXI_BYTE = 0b01010101     # the same constant replicated over the four fields of a byte
 
 

@@ -8,8 +8,9 @@ operation, in this order:
     f = scale[c] * float(C) ; f = f + bias[c] ; f = f + skip ; f = max(f, 0)
     level = activation quantizer of the next layer applied to f   (oracle/quantizer.py)
 
-The paper does not say what ReLU does to a NaN; the reading taken is the IEEE 754 maximum
-of two numbers, which returns the operand that is not a NaN: max(NaN, 0) = 0.
+The paper does not say what ReLU does to a NaN.  Reading: ReLU is max(f, 0) as the deep-learning
+frameworks the paper trains in define it, where a NaN operand gives a NaN (the fp32 output f shows
+it to the caller); the quantizer then treats that NaN as its module documents (the value 0).
 """
 from __future__ import annotations
 
@@ -27,6 +28,6 @@ def chain_epilogue(C: np.ndarray, scale: np.ndarray, bias: Optional[np.ndarray],
     if skip is not None:
         f = (f + np.asarray(skip, dtype=np.float32)).astype(np.float32)
     if relu:
-        f = np.fmax(f, np.float32(0))
+        f = np.maximum(f, np.float32(0))     # NaN stays NaN
     levels = quantizer.levels_from_floats(f, False, out_act_mode, alpha1, alpha2)
     return f, levels

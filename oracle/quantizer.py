@@ -11,6 +11,12 @@ Section 4.1: normalise by the step size, saturate, round with bankers rounding.
 The rounding decides an integer from floating point, so it is taken in the precision
 the HIP kernel works in: every operation below is a single-precision IEEE operation
 (numpy float32 arithmetic, round-half-to-even).  Level index = Q^w + 1, or Q^a.
+
+NaN.  Eq. 8-10 are defined on real numbers; a NaN is outside their domain, and the level
+set {-1,0,+1} / {0,1,2} (first constraint of Section 3.3) has no member for it.  Reading:
+a NaN is an invalid input in the same sense as a level index outside {0,1,2} -- it takes the
+VALUE 0 (Q^w = 0, Q^a = 0) and is counted (count_invalid).  The value is assigned explicitly
+below; no floating-point NaN is ever converted to an integer.
 No code is shared with the HIP path (which pre-computes exact thresholds instead of
 dividing).
 """
@@ -25,34 +31,50 @@ def _f32(x):
     return np.asarray(x, dtype=np.float32)
 
 
+def _finite_part(p: np.ndarray):
+    """(is_nan mask, p with every NaN replaced by 0.0 so that the formulas below see numbers only)."""
+    nan = np.isnan(p)
+    return nan, np.where(nan, np.float32(0), p).astype(np.float32)
+
+
+def _values(q: np.ndarray, nan: np.ndarray) -> np.ndarray:
+    """Quantizer output as int8 with the value 0 wherever the input was a NaN."""
+    return np.where(nan, np.int8(0), q.astype(np.int8)).astype(np.int8)
+
+
+def count_invalid(p) -> int:
+    """Inputs outside the quantizers' domain (NaN)."""
+    return int(np.isnan(_f32(p)).sum())
+
+
 def quantize_weight(p, alpha1, alpha2) -> np.ndarray:
     """Eq. 9 in float32; returns values in {-1, 0, +1} as int8."""
-    p = _f32(p)
+    nan, p = _finite_part(_f32(p))
     a1, a2 = np.float32(alpha1), np.float32(alpha2)
-    with np.errstate(invalid="ignore", over="ignore"):
+    with np.errstate(over="ignore"):
         neg = np.rint(np.clip(p / a1, np.float32(-1), np.float32(0)))
         pos = np.rint(np.clip(p / a2, np.float32(0), np.float32(1)))
-    return (neg + pos).astype(np.int8)
+    return _values(neg + pos, nan)
 
 
 def quantize_weight_piecewise(p, alpha1, alpha2) -> np.ndarray:
     """Eq. 8 (the two-case form) in float32."""
-    p = _f32(p)
+    nan, p = _finite_part(_f32(p))
     a1, a2 = np.float32(alpha1), np.float32(alpha2)
-    with np.errstate(invalid="ignore", over="ignore"):
+    with np.errstate(over="ignore"):
         neg = np.rint(np.clip(p / a1, np.float32(-1), np.float32(0)))
         pos = np.rint(np.clip(p / a2, np.float32(0), np.float32(1)))
-    return np.where(p < 0, neg, pos).astype(np.int8)
+    return _values(np.where(p < 0, neg, pos), nan)
 
 
 def quantize_relu_act(p, alpha1, alpha2) -> np.ndarray:
     """Eq. 10 in float32; returns values in {0, 1, 2} as int8."""
-    p = _f32(p)
+    nan, p = _finite_part(_f32(p))
     a1, a2 = np.float32(alpha1), np.float32(alpha2)
-    with np.errstate(invalid="ignore", over="ignore"):
+    with np.errstate(over="ignore"):
         first = np.rint(np.clip(p / a1, np.float32(0), np.float32(1)))
         second = np.rint(np.clip((p - a1) / a2, np.float32(0), np.float32(1)))
-    return (first + second).astype(np.int8)
+    return _values(first + second, nan)
 
 
 def levels_from_floats(p, role_is_weight: bool, act_mode: int, alpha1, alpha2) -> np.ndarray:

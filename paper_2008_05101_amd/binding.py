@@ -25,7 +25,7 @@ EXPORTS = [
     "fatnn_quantize_pack_bordered", "fatnn_bordered_act_init", "fatnn_ternary_conv2d_chain",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
     "fatnn_twobit_conv2d", "fatnn_binary_packed_bytes", "fatnn_pack_binary", "fatnn_binary_gemm",
-    "fatnn_time_next_launch", "fatnn_status_str", "fatnn_version",
+    "fatnn_time_next_launch", "fatnn_set_tuning", "fatnn_level_status", "fatnn_status_str", "fatnn_version",
 ]
 
 
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         l.fatnn_pack_binary.argtypes = [vp, i64, i64, vp, sz, vp, vp]
         l.fatnn_binary_gemm.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
         l.fatnn_time_next_launch.argtypes = [vp, vp]
+        l.fatnn_set_tuning.argtypes = [i32, i32, i32]
+        l.fatnn_level_status.argtypes = [i64]
         l.fatnn_status_str.argtypes = [i32]
         l.fatnn_status_str.restype = ctypes.c_char_p
         l.fatnn_version.restype = i32
@@ -114,14 +116,18 @@ def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
 
 
 def pack_binary(bits: torch.Tensor, out: Optional[torch.Tensor] = None,
-                n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+                n_invalid: Optional[torch.Tensor] = None,
+                          check_levels: bool = False) -> torch.Tensor:
     bits = _dev(bits, torch.int8, "bits")
     rows, K = bits.shape
     if out is None:
         out = torch.empty(max(int(lib().fatnn_binary_packed_bytes(rows, K)), 16), dtype=torch.uint8,
                           device=bits.device)
+    chk = _LevelCheck(check_levels, n_invalid, bits.device)
+    n_invalid = chk.counter
     _check(lib().fatnn_pack_binary(_ptr(bits), rows, K, _ptr(out), out.numel(), _ptr(n_invalid), _stream()),
            "fatnn_pack_binary")
+    chk.finish("fatnn_pack_binary")
     return out
 
 
@@ -133,6 +139,30 @@ def binary_gemm(Wb: torch.Tensor, Ab: torch.Tensor, M: int, N: int, K: int,
     _check(lib().fatnn_binary_gemm(_ptr(Wb), _ptr(Ab), M, N, K, _ptr(out), max(ldc, N), _stream()),
            "fatnn_binary_gemm")
     return out
+
+
+def set_tuning(conv_kernel: int = -1, stream_wps: int = -1, seven_pixel_groups: int = -1) -> None:
+    """fatnn_set_tuning: process-wide measurement switches; -1 keeps a value."""
+    _check(lib().fatnn_set_tuning(conv_kernel, stream_wps, seven_pixel_groups), "fatnn_set_tuning")
+
+
+class _LevelCheck:
+    """check_levels=True of the packing wrappers: a zeroed device counter for the call, read back
+    afterwards (this synchronises the stream) and turned into FATNN_ERR_LEVEL when it is not zero."""
+
+    def __init__(self, enabled: bool, n_invalid: Optional[torch.Tensor], device):
+        self.counter = n_invalid
+        self.enabled = enabled
+        self.before = 0
+        if enabled:
+            if n_invalid is None:
+                self.counter = torch.zeros(1, dtype=torch.int32, device=device)
+            else:
+                self.before = int(n_invalid.item())
+
+    def finish(self, where: str) -> None:
+        if self.enabled:
+            _check(lib().fatnn_level_status(int(self.counter.item()) - self.before), where)
 
 
 def time_next_launch(start_event: Optional[int], stop_event: Optional[int]) -> None:
@@ -183,7 +213,8 @@ def _dims4(layout: int, levels: torch.Tensor):
 
 
 def pack_ternary(levels: torch.Tensor, role: int, layout: int = ROWMAJOR_K,
-                 out: Optional[torch.Tensor] = None, n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+                 out: Optional[torch.Tensor] = None, n_invalid: Optional[torch.Tensor] = None,
+                          check_levels: bool = False) -> torch.Tensor:
     """fatnn_pack_ternary: int8 level tensor -> packed plane words (uint8 buffer)."""
     levels = _dev(levels, torch.int8, "levels")
     dims, shape = _dims4(layout, levels)
@@ -191,21 +222,28 @@ def pack_ternary(levels: torch.Tensor, role: int, layout: int = ROWMAJOR_K,
     nbytes = packed_bytes(role, rows, K) if K >= 1 else 0
     if out is None:
         out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=levels.device)
+    chk = _LevelCheck(check_levels, n_invalid, levels.device)
+    n_invalid = chk.counter
     _check(lib().fatnn_pack_ternary(_ptr(levels), layout, dims, role, _ptr(out), out.numel(),
                                     _ptr(n_invalid), _stream()), "fatnn_pack_ternary")
+    chk.finish("fatnn_pack_ternary")
     return out
 
 
 def pack_twobit(codes: torch.Tensor, role: int = ACT, layout: int = ROWMAJOR_K,
-                out: Optional[torch.Tensor] = None, n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, n_invalid: Optional[torch.Tensor] = None,
+                          check_levels: bool = False) -> torch.Tensor:
     codes = _dev(codes, torch.int8, "codes")
     dims, shape = _dims4(layout, codes)
     rows, K = _rows_k(layout, shape)
     nbytes = packed_bytes(role, rows, K) if K >= 1 else 0
     if out is None:
         out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=codes.device)
+    chk = _LevelCheck(check_levels, n_invalid, codes.device)
+    n_invalid = chk.counter
     _check(lib().fatnn_pack_twobit(_ptr(codes), layout, dims, role, _ptr(out), out.numel(), _ptr(n_invalid),
                                    _stream()), "fatnn_pack_twobit")
+    chk.finish("fatnn_pack_twobit")
     return out
 
 
@@ -214,7 +252,8 @@ def bordered_act_bytes(B: int, H: int, W: int, C: int, border: int) -> int:
 
 
 def pack_ternary_bordered(levels: torch.Tensor, border: int, act_mode: int, out: Optional[torch.Tensor] = None,
-                          n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+                          n_invalid: Optional[torch.Tensor] = None,
+                          check_levels: bool = False) -> torch.Tensor:
     """fatnn_pack_ternary_bordered: NHWC int8 levels -> bordered packed activations."""
     levels = _dev(levels, torch.int8, "levels")
     if levels.dim() != 4:
@@ -223,13 +262,17 @@ def pack_ternary_bordered(levels: torch.Tensor, border: int, act_mode: int, out:
     dims = (ctypes.c_int64 * 4)(B, H, W, C)
     if out is None:
         out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8, device=levels.device)
+    chk = _LevelCheck(check_levels, n_invalid, levels.device)
+    n_invalid = chk.counter
     _check(lib().fatnn_pack_ternary_bordered(_ptr(levels), dims, border, act_mode, _ptr(out), out.numel(),
                                              _ptr(n_invalid), _stream()), "fatnn_pack_ternary_bordered")
+    chk.finish("fatnn_pack_ternary_bordered")
     return out
 
 
 def pack_twobit_bordered(codes: torch.Tensor, border: int, out: Optional[torch.Tensor] = None,
-                         n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+                         n_invalid: Optional[torch.Tensor] = None,
+                          check_levels: bool = False) -> torch.Tensor:
     codes = _dev(codes, torch.int8, "codes")
     if codes.dim() != 4:
         raise ValueError("codes must be NHWC")
@@ -237,14 +280,18 @@ def pack_twobit_bordered(codes: torch.Tensor, border: int, out: Optional[torch.T
     dims = (ctypes.c_int64 * 4)(B, H, W, C)
     if out is None:
         out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8, device=codes.device)
+    chk = _LevelCheck(check_levels, n_invalid, codes.device)
+    n_invalid = chk.counter
     _check(lib().fatnn_pack_twobit_bordered(_ptr(codes), dims, border, _ptr(out), out.numel(), _ptr(n_invalid),
                                             _stream()), "fatnn_pack_twobit_bordered")
+    chk.finish("fatnn_pack_twobit_bordered")
     return out
 
 
 def quantize_pack(x: torch.Tensor, role: int, act_mode: int, alpha1: float, alpha2: float,
                   layout: int = ROWMAJOR_K, out: Optional[torch.Tensor] = None,
-                  n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+                  n_invalid: Optional[torch.Tensor] = None,
+                          check_levels: bool = False) -> torch.Tensor:
     """fatnn_quantize_pack: float32 tensor -> packed plane words through the paper's quantizer."""
     x = _dev(x, torch.float32, "x")
     dims, shape = _dims4(layout, x)
@@ -252,14 +299,18 @@ def quantize_pack(x: torch.Tensor, role: int, act_mode: int, alpha1: float, alph
     nbytes = packed_bytes(role, rows, K) if K >= 1 else 0
     if out is None:
         out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    chk = _LevelCheck(check_levels, n_invalid, x.device)
+    n_invalid = chk.counter
     _check(lib().fatnn_quantize_pack(_ptr(x), layout, dims, role, act_mode, alpha1, alpha2, _ptr(out), out.numel(),
                                      _ptr(n_invalid), _stream()), "fatnn_quantize_pack")
+    chk.finish("fatnn_quantize_pack")
     return out
 
 
 def quantize_pack_bordered(x: torch.Tensor, border: int, act_mode: int, alpha1: float, alpha2: float,
                            out: Optional[torch.Tensor] = None,
-                           n_invalid: Optional[torch.Tensor] = None) -> torch.Tensor:
+                           n_invalid: Optional[torch.Tensor] = None,
+                          check_levels: bool = False) -> torch.Tensor:
     x = _dev(x, torch.float32, "x")
     if x.dim() != 4:
         raise ValueError("x must be NHWC")
@@ -267,9 +318,12 @@ def quantize_pack_bordered(x: torch.Tensor, border: int, act_mode: int, alpha1: 
     dims = (ctypes.c_int64 * 4)(B, H, W, C)
     if out is None:
         out = torch.empty(max(bordered_act_bytes(B, H, W, C, border), 16), dtype=torch.uint8, device=x.device)
+    chk = _LevelCheck(check_levels, n_invalid, x.device)
+    n_invalid = chk.counter
     _check(lib().fatnn_quantize_pack_bordered(_ptr(x), dims, border, act_mode, alpha1, alpha2, _ptr(out),
                                               out.numel(), _ptr(n_invalid), _stream()),
            "fatnn_quantize_pack_bordered")
+    chk.finish("fatnn_quantize_pack_bordered")
     return out
 
 

@@ -4,6 +4,7 @@
 #include "../../include/fatnn.h"
 #include "fatnn_device.h"
 
+#include <atomic>
 #include <math.h>
 #include <stdlib.h>
 
@@ -12,6 +13,41 @@ using namespace fatnn;
 namespace fatnn {
 namespace {
 thread_local LaunchTiming g_timing = {nullptr, nullptr};
+}
+// The measurement switches: process-wide atomics whose initial values are read from the
+// environment exactly once, on first use (the initialisation of a function-local static is
+// thread-safe); fatnn_set_tuning overwrites them; launches only read them.
+namespace {
+struct TuningState {
+    std::atomic<int> force_tiled, stream_wps, u7_mode;
+    TuningState() {
+        const char* e = getenv("FATNN_CONV_KERNEL");
+        force_tiled.store(e != nullptr && e[0] == 't' ? 1 : 0);
+        e = getenv("FATNN_STREAM_WPS");
+        const int w = e != nullptr ? atoi(e) : 0;
+        stream_wps.store(w > 0 ? w : 0);
+        e = getenv("FATNN_STREAM_U7");
+        u7_mode.store((e != nullptr && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 1);
+    }
+};
+TuningState& tuning_state() {
+    static TuningState s;
+    return s;
+}
+}  // namespace
+Tuning tuning() {
+    TuningState& s = tuning_state();
+    Tuning v;
+    v.force_tiled = s.force_tiled.load(std::memory_order_relaxed) != 0;
+    v.stream_wps = s.stream_wps.load(std::memory_order_relaxed);
+    v.u7_mode = s.u7_mode.load(std::memory_order_relaxed);
+    return v;
+}
+void set_tuning(int force_tiled, int stream_wps, int u7_mode) {
+    TuningState& s = tuning_state();
+    if (force_tiled >= 0) s.force_tiled.store(force_tiled != 0 ? 1 : 0, std::memory_order_relaxed);
+    if (stream_wps >= 0) s.stream_wps.store(stream_wps, std::memory_order_relaxed);
+    if (u7_mode >= 0) s.u7_mode.store(u7_mode, std::memory_order_relaxed);
 }
 LaunchTiming take_launch_timing() {
     const LaunchTiming t = g_timing;
@@ -173,13 +209,11 @@ void set_ternary_consts(GemmParams& p, const void* Wp, int64_t M, int64_t K, int
     }
 }
 
-// Which convolution kernel serves a call.  FATNN_CONV_KERNEL=tiled overrides the
-// choice (for measurements).
+// Which convolution kernel serves a call.  Tuning::force_tiled overrides the choice (for
+// measurements).
 bool want_stream(int op, int R, int S, int Cw, int stride) {
     if (!stream_supported(op, R, S, Cw, stride)) return false;
-    const char* e = getenv("FATNN_CONV_KERNEL");
-    if (e != nullptr && e[0] == 't') return false;
-    return true;
+    return !tuning().force_tiled;
 }
 
 struct ChainArgs {
@@ -310,6 +344,10 @@ int quant_setup(int role, int act_mode, float alpha1, float alpha2, float* t1, f
     const bool relu = role == FATNN_ACT && act_mode == FATNN_RELU;
     if (!exact_threshold(1, relu, alpha1, alpha2, t1) || !exact_threshold(2, relu, alpha1, alpha2, t2))
         return FATNN_ERR_UNSUPPORTED;
+    // A NaN is outside the quantizers' domain: it is packed as the VALUE 0 (and counted where the call
+    // has a counter).  Value 0 is level 1 = planes (0, 1) for weights and symmetric activations, level 0
+    // = planes (0, 0) for ReLU-mode activations; both comparisons are false for a NaN, so only the low
+    // plane bit needs to be supplied.
     *nan_lo = relu ? 0u : 1u;
     return FATNN_OK;
 }
@@ -592,6 +630,14 @@ int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B,
     return run_conv(Wp, Xp, x_layout, B, Cin, H, W, Cout, R, S, stride, pad, cs,
                     basis == FATNN_BASIS_TERNARY ? OP_TWOBIT_TERNARY : OP_XOR_PAIR, FATNN_SYM, Y, nullptr, nullptr,
                     nullptr, stream);
+}
+
+int fatnn_level_status(int64_t n_invalid_host) { return n_invalid_host == 0 ? FATNN_OK : FATNN_ERR_LEVEL; }
+
+int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups) {
+    if (conv_kernel > 1 || stream_wps > 8 || seven_pixel_groups > 2) return FATNN_ERR_UNSUPPORTED;
+    fatnn::set_tuning(conv_kernel, stream_wps, seven_pixel_groups);
+    return FATNN_OK;
 }
 
 int fatnn_time_next_launch(void* start_event, void* stop_event) {

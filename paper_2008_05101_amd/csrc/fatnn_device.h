@@ -90,6 +90,16 @@ struct LaunchTiming {
 };
 LaunchTiming take_launch_timing();
 
+// Measurement switches (process-wide; see fatnn_set_tuning).  Initial values come from the environment,
+// read once: FATNN_CONV_KERNEL=tiled, FATNN_STREAM_WPS=n, FATNN_STREAM_U7=0|1|2.
+struct Tuning {
+    bool force_tiled;   // convolutions go to the LDS-tiled kernel even where the streaming one applies
+    int stream_wps;     // wavefronts per SIMD of the streaming kernel (0 = planned)
+    int u7_mode;        // seven-pixel groups: 0 off, 1 by the size rule, 2 wherever a kernel exists
+};
+Tuning tuning();
+void set_tuning(int force_tiled, int stream_wps, int u7_mode);   // a negative value keeps the current one
+
 // Column-streaming convolution (weights resident in registers, activations through
 // the scalar cache).  Input: bordered packed activations [B][Hp][Wp][Cw] (+ slack),
 // i.e. padding is physical.  Output is NHWC: element (n, m) at n * ldc_n + m.

@@ -33,7 +33,7 @@
 // instructions per 32 elements; the two-bit form of Eq. 2 needs 4 + 4.
 #include "fatnn_device.h"
 
-#include <stdlib.h>
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
@@ -403,13 +403,15 @@ __global__ __launch_bounds__(256 * (CWT / CW)) void stream_conv_kernel(const Str
                 f = f + bs;
                 f = f + sk[u];
                 if (p.relu) {
-                    f = fmaxf(f, 0.0f);
+                    // max(f, 0) that keeps a NaN a NaN (v_max_f32 alone would return the 0); the fp32
+                    // output then shows the NaN, and the quantizer below gives it the value 0
+                    f = (f < 0.0f) ? 0.0f : f;
                     asm volatile("" : "+v"(f));   // keeps this a scalar branch instead of a per-lane select
                 }
                 if (p.Cf != nullptr)
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(f), frsrc, (int)lane_byte,
                                                           (int)((o0 + (uint32_t)u * ldc) * 4u), kStreamOut);
-                // wave-wide comparisons; a NaN compares false and gets the low bit the quantizer formula gives it
+                // wave-wide comparisons; a NaN compares false and is given the value 0 (low plane bit nan_lo)
                 uint64_t lo = __ballot(f >= p.t1);
                 if (p.nan_lo != 0u) lo |= __ballot(f != f);
                 lo &= ok_mask;
@@ -488,20 +490,31 @@ __global__ __launch_bounds__(256 * (CWT / CW)) void stream_conv_kernel(const Str
 
 // Wavefronts per SIMD that stay resident for a kernel at a workgroup size (asked once per
 // instantiation and workgroup size; the answer depends on the register count the compiler reached).
+// A workgroup has at most 16 wavefronts (four row blocks of up to four wavefronts each).  The slots are
+// atomics: concurrent first calls compute the same value and store it twice, which is harmless.
+constexpr int kMaxWavesPerGroup = 16;
+struct OccupancyCache {
+    std::atomic<int> slot[kMaxWavesPerGroup + 1];
+};
 template <typename Kernel>
-int resident_waves_per_simd(Kernel kernel, int wpb, size_t lds, int* cache) {
-    if (cache[wpb] == 0) {
+int resident_waves_per_simd(Kernel kernel, int waves_per_group, size_t lds, OccupancyCache& cache) {
+    if (waves_per_group < 1 || waves_per_group > kMaxWavesPerGroup) return 1;
+    int v = cache.slot[waves_per_group].load(std::memory_order_relaxed);
+    if (v == 0) {
         int nblk = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, kernel, 64 * wpb, lds) != hipSuccess || nblk < 1) nblk = 1;
-        const int waves = nblk * wpb / 4;
-        cache[wpb] = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, kernel, 64 * waves_per_group, lds) != hipSuccess ||
+            nblk < 1)
+            nblk = 1;
+        const int waves = nblk * waves_per_group / 4;
+        v = waves < 1 ? 1 : (waves > 8 ? 8 : waves);
+        cache.slot[waves_per_group].store(v, std::memory_order_relaxed);
     }
-    return cache[wpb];
+    return v;
 }
 
 // Number of ranges of pixel groups (= wavefronts per block of 64 output channels).  All
 // wavefronts are meant to be resident at once, the same number on every SIMD, and each
-// should see enough groups to amortise loading its weights.  FATNN_STREAM_WPS sets the
+// should see enough groups to amortise loading its weights.  Tuning::stream_wps forces the
 // wavefronts per SIMD (for measurements).
 int plan_ranges(int64_t mblocks, int64_t ngroups, int occ) {
     // As many wavefronts per SIMD as stay resident, up to 6 (more only adds weight-load traffic at
@@ -511,11 +524,8 @@ int plan_ranges(int64_t mblocks, int64_t ngroups, int occ) {
     int64_t wps = occ < 6 ? occ : 6;
     while (wps > 4 && ngroups * mblocks < 3 * 1024 * wps) --wps;
     while (wps > 1 && ngroups * mblocks < 1024 * wps) --wps;
-    const char* e = getenv("FATNN_STREAM_WPS");
-    if (e != nullptr && atoi(e) > 0) {
-        wps = atoi(e);
-        if (wps > occ) wps = occ;
-    }
+    const int forced = tuning().stream_wps;
+    if (forced > 0) wps = forced < occ ? forced : occ;
     int64_t ranges = (1024 * wps) / mblocks;
     if (ranges < 1) ranges = 1;
     if (ranges > ngroups) ranges = ngroups;
@@ -532,8 +542,9 @@ int launch_inst(StreamParams p, int64_t out_rows, int64_t Wo, hipStream_t stream
     const int mblocks = (p.M + 63) / 64;
     const int wpb = mblocks < 4 ? mblocks : 4;        // row blocks per workgroup
     const int waves = wpb * KH;
+    static_assert(4 * KH <= kMaxWavesPerGroup, "occupancy cache too small for this workgroup");
     const size_t lds = KH > 1 ? (size_t)wpb * 2 * (KH - 1) * U * 64 * sizeof(int32_t) : 0;
-    auto launch = [&](auto kernel, int* cache) {
+    auto launch = [&](auto kernel, OccupancyCache& cache) {
         const int occ = resident_waves_per_simd(kernel, waves, lds, cache);
         const int ranges = plan_ranges((int64_t)mblocks * KH, ngroups, occ);
         p.gq = (int32_t)(ngroups / ranges);
@@ -545,13 +556,13 @@ int launch_inst(StreamParams p, int64_t out_rows, int64_t Wo, hipStream_t stream
     };
     if (p.Xn != nullptr) {
         if constexpr (OP == OP_TERNARY) {
-            static int cache[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+            static OccupancyCache cache{};
             return launch(stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_CHAIN>, cache);
         } else {
             return -3;
         }
     }
-    static int cache[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    static OccupancyCache cache{};
     return launch(stream_conv_kernel<OP, R, CW, CWT, ST, U, EPI_PLAIN>, cache);
 }
 
@@ -584,18 +595,17 @@ constexpr int alt_u(int R, int CW, int ST) {
     return (CW == 4 || CW == 8 || CW == 16) ? 7 : 0;
 }
 
-// Output pixels per group for this call.  FATNN_STREAM_U7=0 switches the second group size off,
-// =2 uses it wherever a kernel exists (for tests of those kernels on small inputs).
+// Output pixels per group for this call.  Tuning::u7_mode 0 switches the second group size off,
+// 2 uses it wherever a kernel exists (for tests of those kernels on small inputs).
 int pick_group_size(int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo, int64_t mblocks) {
     const int alt = alt_u(R, Cw, stride);
     if (alt != 0 && Wo % alt == 0) {
-        const char* e = getenv("FATNN_STREAM_U7");
-        const char mode = e == nullptr ? '1' : e[0];
+        const int mode = tuning().u7_mode;
         // 128 channels: always (with the two-word wavefront pairs that go with it, measured 15-20 % faster
         // from batch 2 to 32 at 28x28 and equal beyond); 256 and 512 channels: only where the larger groups
         // still leave every SIMD three of them (measured: slower at 1-2 per SIMD, faster from 3.5)
         const int64_t enough = Cw <= 4 ? 0 : 3 * 1024;
-        if (mode == '2' || (mode != '0' && out_rows * (Wo / alt) * mblocks >= enough)) return alt;
+        if (mode == 2 || (mode != 0 && out_rows * (Wo / alt) * mblocks >= enough)) return alt;
     }
     return group_u(R, Cw, stride);
 }

@@ -25,3 +25,14 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tuning():
+    """Sets the library's process-wide measurement switches for one test and restores the defaults."""
+    import paper_2008_05101_amd as fatnn
+
+    def set_(**kw):
+        fatnn.set_tuning(**kw)
+    yield set_
+    fatnn.set_tuning(conv_kernel=0, stream_wps=0, seven_pixel_groups=1)

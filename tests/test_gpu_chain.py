@@ -83,9 +83,9 @@ def test_chain_epilogue_exact(Cin, Cout, H, W, R, stride, pad, in_mode, out_mode
 @pytest.mark.parametrize("Cin,Cout,H,W,use_skip", [(256, 256, 7, 7, True), (256, 96, 6, 14, False),
                                                    (512, 128, 7, 7, True), (512, 64, 4, 14, False),
                                                    (128, 128, 5, 28, True), (128, 96, 7, 7, False)])
-def test_chain_epilogue_groups_of_seven(monkeypatch, Cin, Cout, H, W, use_skip):
+def test_chain_epilogue_groups_of_seven(tuning, Cin, Cout, H, W, use_skip):
     """The chaining epilogue of the seven-pixel-group kernels (chosen by default only for large batches)."""
-    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+    tuning(seven_pixel_groups=2)
     test_chain_epilogue_exact(Cin, Cout, H, W, 3, 1, 1, 1, 1, 1, use_skip, True)
 
 
@@ -118,8 +118,8 @@ def test_chain_epilogue_nan_and_inf_in_the_skip(relu, out_mode):
 
 
 @pytest.mark.parametrize("Cin,Cout,H,W,use_skip", [(128, 256, 9, 14, True), (256, 512, 6, 14, False)])
-def test_chain_epilogue_stride2_groups_of_seven(monkeypatch, Cin, Cout, H, W, use_skip):
-    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+def test_chain_epilogue_stride2_groups_of_seven(tuning, Cin, Cout, H, W, use_skip):
+    tuning(seven_pixel_groups=2)
     test_chain_epilogue_exact(Cin, Cout, H, W, 3, 2, 1, 1, 1, 1, use_skip, True)
 
 

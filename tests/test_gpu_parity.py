@@ -96,6 +96,34 @@ def test_pack_counts_invalid_levels_and_packs_them_as_zero():
         assert np.array_equal(body, L)
 
 
+def test_check_levels_raises_err_level():
+    """First constraint of Section 3.3: an input outside the level set is an error the binding can raise."""
+    rnd = np.random.default_rng(19)
+    L = rnd.integers(0, 3, size=(8, 64), dtype=np.int8)
+    for role in (0, 1):
+        fatnn.pack_ternary(dev(L), role, check_levels=True)                    # clean input: no error
+    Lb = L.copy()
+    Lb[2, 7] = 3
+    with pytest.raises(fatnn.FatnnError) as e:
+        fatnn.pack_ternary(dev(Lb), fatnn.ACT, check_levels=True)
+    assert e.value.status == -3
+    # a caller's own counter keeps counting; only this call's increment decides
+    cnt = torch.full((1,), 5, dtype=torch.int32, device=DEV)
+    fatnn.pack_ternary(dev(L), fatnn.ACT, n_invalid=cnt, check_levels=True)
+    with pytest.raises(fatnn.FatnnError):
+        fatnn.pack_ternary(dev(Lb), fatnn.WEIGHT, n_invalid=cnt, check_levels=True)
+    assert int(cnt.item()) == 6
+    x4 = rnd.integers(0, 3, size=(1, 4, 4, 32), dtype=np.int8)
+    x4[0, 1, 2, 3] = -1
+    with pytest.raises(fatnn.FatnnError):
+        fatnn.pack_ternary_bordered(dev(x4), 1, fatnn.RELU, check_levels=True)
+    xf = rnd.standard_normal((4, 64)).astype(np.float32)
+    fatnn.quantize_pack(dev(xf), fatnn.ACT, fatnn.RELU, 0.7, 0.9, check_levels=True)
+    xf[0, 0] = np.nan
+    with pytest.raises(fatnn.FatnnError):
+        fatnn.quantize_pack(dev(xf), fatnn.ACT, fatnn.RELU, 0.7, 0.9, check_levels=True)
+
+
 def test_pack_layouts_agree():
     rnd = np.random.default_rng(10)
     w = rnd.integers(0, 3, size=(6, 3, 3, 64), dtype=np.int8)          # OHWI
@@ -289,9 +317,9 @@ def test_conv_parity_small(Cin, Cout, H, W, R, stride, pad, mode, bordered):
 @pytest.mark.parametrize("Cin,Cout,H,W", [(256, 64, 7, 7), (256, 130, 9, 14), (512, 64, 7, 7), (512, 200, 5, 14),
                                           (256, 64, 3, 21), (128, 128, 6, 28), (128, 70, 7, 7)])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_conv_parity_groups_of_seven(monkeypatch, Cin, Cout, H, W, mode):
+def test_conv_parity_groups_of_seven(tuning, Cin, Cout, H, W, mode):
     """The seven-pixel-group kernels (normally chosen only for large batches) on small inputs."""
-    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+    tuning(seven_pixel_groups=2)
     rnd = np.random.default_rng(Cin + Cout + H + W + mode)
     Lw = rnd.integers(0, 3, size=(Cout, 3, 3, Cin), dtype=np.int8)
     Lx = rnd.integers(0, 3, size=(5, H, W, Cin), dtype=np.int8)
@@ -306,10 +334,10 @@ def test_conv_parity_groups_of_seven(monkeypatch, Cin, Cout, H, W, mode):
 @pytest.mark.parametrize("Cin,Cout,H,W,R,stride,pad", [(64, 70, 12, 10, 3, 2, 1), (128, 130, 7, 7, 3, 1, 1),
                                                        (64, 128, 14, 14, 1, 2, 0), (256, 64, 7, 9, 1, 1, 0)])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_conv_bordered_input_on_the_tiled_kernel(monkeypatch, Cin, Cout, H, W, R, stride, pad, mode):
+def test_conv_bordered_input_on_the_tiled_kernel(tuning, Cin, Cout, H, W, R, stride, pad, mode):
     """The fallback that serves bordered inputs the streaming kernel cannot take (tensors of 4 GiB and
     more): the LDS-tiled kernel reading the bordered layout, forced here on small inputs."""
-    monkeypatch.setenv("FATNN_CONV_KERNEL", "tiled")
+    tuning(conv_kernel=1)
     rnd = np.random.default_rng(Cin + Cout + H + R + stride + mode + 1)
     Lw = rnd.integers(0, 3, size=(Cout, R, R, Cin), dtype=np.int8)
     Lx = rnd.integers(0, 3, size=(3, H, W, Cin), dtype=np.int8)
@@ -319,9 +347,9 @@ def test_conv_bordered_input_on_the_tiled_kernel(monkeypatch, Cin, Cout, H, W, R
 
 @pytest.mark.parametrize("Cin,Cout,H,W", [(128, 256, 9, 14), (128, 70, 14, 28), (256, 512, 6, 14), (256, 130, 14, 13)])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_conv_stride2_groups_of_seven(monkeypatch, Cin, Cout, H, W, mode):
+def test_conv_stride2_groups_of_seven(tuning, Cin, Cout, H, W, mode):
     """Stride-2 3x3 layers with seven-pixel groups (output rows of 7: W = 13 or 14; 14: W = 28), forced on small inputs."""
-    monkeypatch.setenv("FATNN_STREAM_U7", "2")
+    tuning(seven_pixel_groups=2)
     rnd = np.random.default_rng(Cin + Cout + H + W + mode)
     Lw = rnd.integers(0, 3, size=(Cout, 3, 3, Cin), dtype=np.int8)
     Lx = rnd.integers(0, 3, size=(4, H, W, Cin), dtype=np.int8)

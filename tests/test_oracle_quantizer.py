@@ -107,14 +107,32 @@ def test_chain_epilogue_hand_example():
 
 
 def test_chain_epilogue_nan_through_relu():
-    # max(NaN, 0) = 0 (the operand that is a number); without ReLU the NaN stays and takes the
-    # level that the literal quantizer formula gives it
+    # ReLU keeps a NaN a NaN (the fp32 output shows it); the quantizer gives a NaN the value 0,
+    # which is level 0 for ReLU-mode outputs and level 1 for symmetric ones
     from oracle import chain
     C = np.array([[[[4, 4]]]], np.int32)
     scale = np.array([1.0, 1.0], np.float32)
     skip = np.array([[[[np.nan, 0.0]]]], np.float32)
-    f, lv = chain.chain_epilogue(C, scale, None, skip, True, 1, 1.0, 1.0)
-    assert f.reshape(-1).tolist() == [0.0, 4.0] and lv.reshape(-1).tolist() == [0, 2]
-    f2, lv2 = chain.chain_epilogue(C, scale, None, skip, False, 1, 1.0, 1.0)
-    assert np.isnan(f2.reshape(-1)[0]) and f2.reshape(-1)[1] == 4.0
-    assert lv2.reshape(-1)[0] == q.levels_from_floats(np.array([np.nan], np.float32), False, 1, 1.0, 1.0)[0]
+    for relu in (True, False):
+        f, lv = chain.chain_epilogue(C, scale, None, skip, relu, 1, 1.0, 1.0)
+        assert np.isnan(f.reshape(-1)[0]) and f.reshape(-1)[1] == 4.0
+        assert lv.reshape(-1).tolist() == [0, 2]
+        f, lv = chain.chain_epilogue(C, scale, None, skip, relu, 0, 1.0, 1.0)
+        assert np.isnan(f.reshape(-1)[0]) and lv.reshape(-1).tolist() == [1, 2]
+    # a negative number still goes to 0 under ReLU, and -inf too
+    skip2 = np.array([[[[-10.0, -np.inf]]]], np.float32)
+    f, lv = chain.chain_epilogue(C, scale, None, skip2, True, 1, 1.0, 1.0)
+    assert f.reshape(-1).tolist() == [0.0, 0.0] and lv.reshape(-1).tolist() == [0, 0]
+
+
+def test_quantizers_give_nan_the_value_zero_and_count_it():
+    import warnings
+    x = np.array([np.nan, -3.0, np.nan, 0.2, 5.0, np.inf, -np.inf], np.float32)
+    with warnings.catch_warnings():
+        warnings.simplefilter("error")          # no invalid-value cast, no NaN arithmetic warning
+        assert q.quantize_weight(x, 0.7, 0.9).tolist() == [0, -1, 0, 0, 1, 1, -1]
+        assert q.quantize_weight_piecewise(x, 0.7, 0.9).tolist() == [0, -1, 0, 0, 1, 1, -1]
+        assert q.quantize_relu_act(x, 0.7, 0.9).tolist() == [0, 0, 0, 0, 2, 2, 0]
+        assert q.levels_from_floats(x, True, 0, 0.7, 0.9).tolist() == [1, 0, 1, 1, 2, 2, 0]
+        assert q.levels_from_floats(x, False, 1, 0.7, 0.9).tolist() == [0, 0, 0, 0, 2, 2, 0]
+    assert q.count_invalid(x) == 2 and q.count_invalid(x[1:2]) == 0
