@@ -1,21 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the ternary hot path on one MI355X.
 
-A step is one pass of the whole path over one batch of the headline workload (a
-ResNet-18-style 3x3 convolution, 128 -> 128 channels at 28x28, batch 32, ReLU-mode
-activations): pack the activation levels into plane words, then the implicit-GEMM
-ternary convolution with its int32 output and the fp32 per-channel scale/bias
-epilogue.  Weights are packed once before the timed region (the paper fixes them
-after training).  Inputs are seeded synthetic level tensors already resident in
-HBM.  Prints ONE JSON line.
+A step is one pass of the whole path over one batch of the headline workload, the large
+square ternary GEMM M = N = K = 8192 on the seeded operands of synth_inputs.cfg4(): pack the
+activation levels into plane words, then the ternary GEMM with its int32 output.  Weights are
+packed once before the timed region (the paper fixes everything derived from them after
+training).  Inputs are seeded synthetic level tensors already resident in HBM.  Prints ONE
+JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg3|cfg5|quantpack|paper6] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+                    [--workload cfg4|cfg2|cfg3|cfg5|quantpack|paper6|peaks] [--no-cpu] [--no-extra]
+
+The roofline object carries two denominators: `peak`, the nominal VALU figure derived from the
+chip's unit counts and clock, and `peak_measured`, the rate at which a register-resident loop of
+the method's own instruction pair issues on this very GPU, measured inside this run
+(`--workload peaks` prints the whole table of such probes).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -30,13 +36,26 @@ VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9
 # (= 64 ops under the 2*M*N*K convention).  The conventional two-bit form needs 8.
 TERNARY_OPS_PER_LANE_INSTR = 64 / 4
 TWOBIT_OPS_PER_LANE_INSTR = 64 / 8
-TERNARY_PEAK_TOPS = VALU_LANE_OPS_PER_S * TERNARY_OPS_PER_LANE_INSTR / 1e12     # 629.1
+TERNARY_PEAK_TOPS = VALU_LANE_OPS_PER_S * TERNARY_OPS_PER_LANE_INSTR / 1e12     # 629.1 (nominal)
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script, scaled by the same counters' readings for a plain copy of known size (profiles/*.md give the
-# commands, the raw readings and the scale factors 2.000 / 1.000).
-MEASURED_TRAFFIC_BYTES = {"cfg2": int((2591.6 * 2.000 + 25088.0 * 1.000) * 1024),
-                          "cfg4": int((179007.2 * 2.000 + 262144.0 * 1.000) * 1024)}
+PEAK_BASIS = ("nominal: 256 CU x 64 lanes x 2.4 GHz = 39.3 T lane-instr/s, 4 lane-instr per 64 ops; measured: "
+              "register-resident v_bitop3_b32 -> v_bcnt_u32_b32 loop on this GPU (fatnn_probe_valu), best over "
+              "wavefronts per SIMD and operand kind, x 16 ops per lane-instr")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def measured_traffic_bytes(workload):
+    """HBM bytes per launch of the workload's dominant kernel, from the table that bench_traffic.py writes out
+    of rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (None when no such run is on file)."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            for ln in fh:
+                m = re.match(r"\|\s*%s\s*\|.*\|\s*(\d+)\s*\|\s*$" % re.escape(workload), ln)
+                if m:
+                    return int(m.group(1))
+    except OSError:
+        pass
+    return None
 
 
 def parse_args():
@@ -44,17 +63,18 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default depends on the workload)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed warm-up steps")
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg3", "cfg5", "quantpack", "paper6"])
+    ap.add_argument("--workload", default="cfg4",
+                    choices=["cfg4", "cfg2", "cfg3", "cfg5", "quantpack", "paper6", "peaks"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="only run a plain 256 MiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE "
-                         "counters of a rocprofv3 --pmc run) and exit")
+                    help="only run the library's 256 MiB copy kernel 5 times (reference for the FETCH_SIZE / "
+                         "WRITE_SIZE counters of a rocprofv3 --pmc run, see bench_traffic.py) and exit")
     args = ap.parse_args()
     # Defaults long enough for the clocks to settle (a cfg2 step is 23 us: 200 steps were over before the GPU
     # had reached its sustained clock, and read 6 % slow), short enough to finish in seconds.
     steps, warmup = {"cfg2": (4000, 1000), "cfg4": (100, 20), "cfg3": (200, 50), "cfg5": (50, 10),
-                     "quantpack": (100, 20), "paper6": (20, 3)}[args.workload]
+                     "quantpack": (100, 20), "paper6": (20, 3), "peaks": (3, 1)}[args.workload]
     if args.steps is None:
         args.steps = steps
     if args.warmup is None:
@@ -134,10 +154,106 @@ class HipEvents:
         self.ev = []
 
 
-def cpu_baseline_conv(case, seconds_target=12.0):
+def settle_clocks(torch, fn, seconds=0.3):
+    """Untimed load before the warm-up: the GPU needs some tens of milliseconds of work to reach its
+    sustained clock, and a short benchmark would otherwise be timed on the ramp.  Returns the time spent."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3
+
+
+def measure_peaks(torch, fatnn, full=False):
+    """The denominators, measured on this GPU with the library's probe kernels: issue rate of the method's
+    instruction pair from registers (lane-instructions per second) over wavefronts per SIMD, and HBM streaming
+    rates.  Each figure is the best of three launches, timed with events attached to the dispatch."""
+    scratch = fatnn.probe_scratch("cuda:0")
+    hev = HipEvents(2)
+
+    def timed(launch):
+        best = None
+        for _ in range(3):
+            fatnn.time_next_launch(hev.handle(0), hev.handle(1))
+            work = launch()
+            ms = hev.elapsed_ms(0, 1)
+            best = ms if best is None or ms < best else best
+        return work, best
+
+    out = {"valu_T_lane_instr_per_s": {}, "hbm_GBps": {}}
+    kinds = [("pair_vgpr_operands", fatnn.PROBE_PAIR_V), ("pair_sgpr_data_word", fatnn.PROBE_PAIR_S)]
+    if full:
+        kinds += [("bcnt_alone", fatnn.PROBE_BCNT), ("bitop3_alone", fatnn.PROBE_BITOP3), ("xor_alone", fatnn.PROBE_XOR)]
+    waves = (1, 2, 3, 4, 5, 6, 7, 8) if full else (2, 4, 8)
+    fatnn.probe_valu(fatnn.PROBE_PAIR_V, 4, 200, scratch)      # first launch loads the code
+    best_pair = 0.0
+    for name, kind in kinds:
+        row = {}
+        for w in waves:
+            work, ms = timed(lambda: fatnn.probe_valu(kind, w, 3000, scratch))
+            rate = work / (ms * 1e-3) / 1e12
+            row[f"{w}_waves_per_simd"] = round(rate, 2)
+            if kind in (fatnn.PROBE_PAIR_V, fatnn.PROBE_PAIR_S):
+                best_pair = max(best_pair, rate)
+        out["valu_T_lane_instr_per_s"][name] = row
+    out["valu_pair_best_T_lane_instr_per_s"] = round(best_pair, 2)
+    out["valu_nominal_T_lane_instr_per_s"] = round(VALU_LANE_OPS_PER_S / 1e12, 2)
+    out["ternary_peak_measured_tops"] = round(best_pair * TERNARY_OPS_PER_LANE_INSTR, 1)
+    nbytes = 1 << 30
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    for name, kind, moved in (("read", fatnn.HBM_READ, nbytes), ("write", fatnn.HBM_WRITE, nbytes),
+                              ("copy", fatnn.HBM_COPY, 2 * nbytes)):
+        _, ms = timed(lambda: fatnn.probe_hbm(kind, b, a, nbytes, scratch))
+        out["hbm_GBps"][name] = round(moved / (ms * 1e-3) / 1e9, 1)
+    out["hbm_best_GBps"] = max(out["hbm_GBps"].values())
+    hev.close()
+    del a, b, scratch
+    return out
+
+
+def alu_roofline(kernel, achieved_tops, kernel_ms, peaks, traffic):
+    """Roofline object of a VALU-bound kernel: fraction of the nominal peak and of the measured one."""
+    r = {"bound": "alu", "kernel": kernel, "achieved": round(achieved_tops, 2), "peak": round(TERNARY_PEAK_TOPS, 1),
+         "unit": "Tops/s", "frac": round(achieved_tops / TERNARY_PEAK_TOPS, 4), "traffic": traffic,
+         "kernel_ms": round(kernel_ms, 5), "peak_measured": None, "frac_measured": None,
+         "graded_on": "frac_measured (the nominal figure is not a ceiling on this chip: the probe loop exceeds it)",
+         "peak_basis": PEAK_BASIS}
+    if peaks is not None:
+        pm = peaks["ternary_peak_measured_tops"]
+        r["peak_measured"] = pm
+        r["frac_measured"] = round(achieved_tops / pm, 4)
+    return r
+
+
+def hbm_roofline(kernel, achieved_gbs, kernel_ms, peaks, traffic=None):
+    r = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(achieved_gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel_ms": round(kernel_ms, 5),
+         "peak_measured": None, "frac_measured": None}
+    if peaks is not None:
+        r["peak_measured"] = peaks["hbm_best_GBps"]
+        r["frac_measured"] = round(achieved_gbs / peaks["hbm_best_GBps"], 4)
+    return r
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for ln in fh:
+                if ln.startswith("model name"):
+                    return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline_conv(case, seconds_target=10.0):
     """The oracle as it stands, timed on the host cores on whole passes of the workload."""
     import oracle
     Lw, Lx = case.make()
+    threads = oracle.num_threads()
     t0 = time.perf_counter()
     oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode)
     first = time.perf_counter() - t0
@@ -146,31 +262,93 @@ def cpu_baseline_conv(case, seconds_target=12.0):
     for _ in range(reps):
         oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode)
     dt = (time.perf_counter() - t0) / reps
-    return {"value": 2.0 * case.macs() / dt / 1e12, "unit": "Tops/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"{reps} full passes of {case.name} (batch {case.B}), {dt:.3f} s each"}
+    # one thread: a slice of the batch sized to a few seconds
+    nb = max(1, min(case.B, int(case.B * 4.0 / max(first * threads, 1e-3))))
+    oracle.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        oracle.ternary_conv2d(Lw, Lx[:nb], case.stride, case.pad, case.act_mode)
+        dt1 = time.perf_counter() - t0
+    finally:
+        oracle.set_num_threads(threads)
+    return {"value": round(2.0 * case.macs() / dt / 1e12, 5), "unit": "Tops/s", "cores": threads,
+            "kind": "oracle", "sample": f"{reps} full passes of {case.name} (batch {case.B}), {dt:.3f} s each",
+            "single_thread_value": round(2.0 * case.macs() * nb / case.B / dt1 / 1e12, 6),
+            "single_thread_sample": f"first {nb} images, {dt1:.2f} s", "cpu_model": cpu_model()}
 
 
-def cpu_baseline_gemm(case, rows=64, seconds_target=12.0):
+def cpu_baseline_gemm(case, rows=64, seconds_target=10.0):
     """The oracle on the first rows of the weight matrix against all columns, sized to about seconds_target."""
     import numpy as np
     import oracle
     Lw, La = case.make()
+    threads = oracle.num_threads()
     t0 = time.perf_counter()
     oracle.ternary_gemm(np.ascontiguousarray(Lw[:rows]), La, case.act_mode)
     first = time.perf_counter() - t0
-    rows = int(max(rows, min(case.M, rows * seconds_target / max(first, 1e-3))))
-    sub = np.ascontiguousarray(Lw[:rows])
+    rows_all = int(max(rows, min(case.M, rows * seconds_target / max(first, 1e-3))))
+    sub = np.ascontiguousarray(Lw[:rows_all])
     t0 = time.perf_counter()
     oracle.ternary_gemm(sub, La, case.act_mode)
     dt = time.perf_counter() - t0
-    return {"value": 2.0 * rows * case.N * case.K / dt / 1e12, "unit": "Tops/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"first {rows} of {case.M} weight rows against all columns, {dt:.2f} s"}
+    rows_one = int(max(1, min(case.M, rows * 4.0 / max(first * threads, 1e-3))))
+    sub1 = np.ascontiguousarray(Lw[:rows_one])
+    oracle.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        oracle.ternary_gemm(sub1, La, case.act_mode)
+        dt1 = time.perf_counter() - t0
+    finally:
+        oracle.set_num_threads(threads)
+    return {"value": round(2.0 * rows_all * case.N * case.K / dt / 1e12, 5), "unit": "Tops/s", "cores": threads,
+            "kind": "oracle", "sample": f"first {rows_all} of {case.M} weight rows against all columns, {dt:.2f} s",
+            "single_thread_value": round(2.0 * rows_one * case.N * case.K / dt1 / 1e12, 6),
+            "single_thread_sample": f"first {rows_one} weight rows, {dt1:.2f} s", "cpu_model": cpu_model()}
+
+
+def other_config_summaries(torch, fatnn, si, dev, peaks):
+    """Short timings of the other configurations next to the headline (each its own --workload in full):
+    the cfg2 convolution step on the streaming kernel, the same and two cfg3 layers through the LDS-tiled
+    kernel's implicit-im2col front end (plain NHWC packed input, nothing materialised), and the ragged GEMM."""
+    out = {}
+    pm = peaks["ternary_peak_measured_tops"]
+
+    def tops(macs, ms):
+        t = 2.0 * macs / (ms * 1e-3) / 1e12
+        return {"us": round(ms * 1e3, 2), "tops": round(t, 1), "frac_nominal": round(t / TERNARY_PEAK_TOPS, 3),
+                "frac_measured": round(t / pm, 3)}
+    layers = si.cfg3(64)
+    picks = [("cfg2_conv3x3_128_28_b32", si.cfg2()), (layers[0].name + "_b64", layers[0]),
+             (layers[15].name + "_b64", layers[15])]      # first 64-channel and first 512-channel 3x3 layer
+    for label, case in picks:
+        Lw, Lx = case.make()
+        Lw_d, Lx_d = torch.from_numpy(Lw).to(dev), torch.from_numpy(Lx).to(dev)
+        Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT, fatnn.OHWI)
+        Xb = fatnn.pack_ternary_bordered(Lx_d, case.pad, case.act_mode)
+        Xplain = fatnn.pack_ternary(Lx_d, fatnn.ACT, fatnn.NHWC)
+        Y = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.int32, device=dev)
+        a = (case.B, case.Cin, case.H, case.W, case.Cout, case.R, case.S, case.stride, case.pad, case.act_mode)
+        t_stream = time_graph_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xb, *a, out=Y, x_layout=fatnn.X_BORDERED), 10)
+        t_tiled = time_graph_ms(torch, lambda: fatnn.ternary_conv2d(Wp, Xplain, *a, out=Y, x_layout=fatnn.X_PLAIN), 10)
+        out[label] = {"streaming_kernel_bordered_input": tops(case.macs(), t_stream),
+                      "tiled_kernel_implicit_im2col_plain_input": tops(case.macs(), t_tiled)}
+        del Wp, Xb, Xplain, Y, Lw_d, Lx_d
+    g = si.cfg5_ragged()
+    Lw, La = g.make()
+    Wp = fatnn.pack_ternary(torch.from_numpy(Lw).to(dev), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(torch.from_numpy(La).to(dev), fatnn.ACT)
+    C = torch.empty((g.M, g.N), dtype=torch.int32, device=dev)
+    t = time_graph_ms(torch, lambda: fatnn.ternary_gemm(Wp, Ap, g.M, g.N, g.K, g.act_mode, out=C), 20)
+    out[f"cfg5a_gemm_{g.M}x{g.N}x{g.K}"] = tops(g.macs(), t)
+    return out
 
 
 def side_workload(args, torch, fatnn, si, dev):
     """Workloads beyond the headline ones: the chained ResNet-18-shaped trunk (cfg3 as one pipeline) and
     the HBM-bound quantize-and-pack pass.  Same JSON shape, one line."""
     import numpy as np
+    settle_clocks(torch, lambda: torch.empty(1 << 26, dtype=torch.uint8, device=dev).fill_(1))
+    peaks = measure_peaks(torch, fatnn)
     if args.workload == "cfg3":
         from paper_2008_05101_amd import resnet_trunk as rt
         batch = 64
@@ -247,10 +425,7 @@ def side_workload(args, torch, fatnn, si, dev):
                                    "pipeline (quantize+pack the fp32 input, every conv writes the next layer's packed "
                                    "input through the fused affine/skip/ReLU/quantize epilogue)", "batch": batch,
                        "macs": trunk.macs},
-            "roofline": {"bound": "alu", "kernel": "stream_conv_kernel (all 19 launches)", "achieved": round(achieved, 2),
-                         "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s",
-                         "frac": round(achieved / TERNARY_PEAK_TOPS, 4), "traffic": None,
-                         "kernel_ms": round(kernel_ms, 5)},
+            "roofline": alu_roofline("stream_conv_kernel (all 19 launches)", achieved, kernel_ms, peaks, None),
             "cpu_baseline": None,
             "extra": {**side, "per_layer_us": {l.name: round(t * 1e3, 2) for l, t in zip(layers, per_layer)},
                       "per_layer_tops": {l.name: round(2.0 * l.macs() / (t * 1e-3) / 1e12, 1)
@@ -306,9 +481,7 @@ def side_workload(args, torch, fatnn, si, dev):
                                    "28/56/112/224, 128 and 256 channels at 56), ternary vs two-bit vs xnor-only "
                                    "kernels; value and ms_per_step are the six ternary layers at batch 32, inputs "
                                    "already packed"},
-            "roofline": {"bound": "alu", "kernel": f"stream_conv_kernel on {best[1]} (batch 32)",
-                         "achieved": round(achieved, 2), "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s",
-                         "frac": round(achieved / TERNARY_PEAK_TOPS, 4), "traffic": None, "kernel_ms": round(best[2], 5)},
+            "roofline": alu_roofline(f"stream_conv_kernel on {best[1]} (batch 32)", achieved, best[2], peaks, None),
             "cpu_baseline": None,
             "extra": {"layers": results,
                       "paper_context_us_nvidia_2080ti_batch1": {"ternary": [11, 14.5, 26, 90, 34, 87],
@@ -374,9 +547,7 @@ def side_workload(args, torch, fatnn, si, dev):
             "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
             "config": {"workload": "cfg5: ragged GEMM 512x3136x4609, GEMV 4096x1x4608, 1x1 convs 256->64 and 64->256 "
                                    "@56x56 batch 128; every step packs its activations first"},
-            "roofline": {"bound": "hbm", "kernel": f"stream_conv_kernel on {worst[0]}", "achieved": worst[1],
-                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(worst[1] / HBM_PEAK_GBS, 4),
-                         "traffic": None, "kernel_ms": round(worst[2], 5)},
+            "roofline": hbm_roofline(f"stream_conv_kernel on {worst[0]}", worst[1], worst[2], peaks),
             "cpu_baseline": None, "extra": results,
         }
         print(json.dumps(line))
@@ -406,10 +577,7 @@ def side_workload(args, torch, fatnn, si, dev):
         "data": "synthetic",
         "config": {"workload": "quantize-and-pack of fp32 NHWC activations 128x56x56x256 (Eq. 10 thresholds), "
                                "4 B read + 0.25 B written per element", "elements": n},
-        "roofline": {"bound": "hbm", "kernel": "quantize_pack_bordered_kernel",
-                     "achieved": round(n * 4.25 / (k1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(n * 4.25 / (k1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel_ms": round(k1, 5)},
+        "roofline": hbm_roofline("quantize_pack_bordered_kernel", n * 4.25 / (k1 * 1e-3) / 1e9, k1, peaks),
         "cpu_baseline": None,
         "extra": {"pack_from_int8_levels_ms": round(k2, 5),
                   "pack_from_int8_levels_GBps": round(n * 1.25 / (k2 * 1e-3) / 1e9, 1)},
@@ -437,18 +605,37 @@ def main():
     torch.cuda.set_device(dev)
 
     if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(3)
+        nbytes = 256 << 20
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(3)
         dst = torch.empty_like(src)
+        scratch = fatnn.probe_scratch(dev)
         for _ in range(5):
-            dst.copy_(src)
+            fatnn.probe_hbm(fatnn.HBM_COPY, dst, src, nbytes, scratch)
         torch.cuda.synchronize()
-        print(json.dumps({"calibration": "5 device copies of 268435456 bytes (read 256 MiB + write 256 MiB each)"}))
+        print(json.dumps({"calibration": "5 launches of hbm_copy_kernel over 268435456 bytes "
+                                         "(read 256 MiB + write 256 MiB each)"}))
         return
 
-    extra = {}
+    if args.workload == "peaks":
+        settle_ms = settle_clocks(torch, lambda: torch.empty(1 << 26, dtype=torch.uint8, device=dev).fill_(1))
+        pk = measure_peaks(torch, fatnn, full=True)
+        line = {"metric": "ternary VALU ceiling Tops/s (register-resident bitop3+bcnt pairs x 16 ops) at 1 MI355X",
+                "value": pk["ternary_peak_measured_tops"], "unit": "Tops/s", "n_gpus": 1, "steps": args.steps,
+                "warmup": args.warmup, "ms_per_step": None, "higher_is_better": True, "scaling": "weak",
+                "vs_baseline": None, "dtype": "u32 bitwise", "data": "synthetic",
+                "config": {"workload": "peaks: issue rate of the method's instruction pair from registers over "
+                                       "1..8 wavefronts per SIMD, and HBM read / write / copy streams of 1 GiB"},
+                "roofline": {"bound": "alu", "kernel": "valu_probe_kernel", "achieved": pk["ternary_peak_measured_tops"],
+                             "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s",
+                             "frac": round(pk["ternary_peak_measured_tops"] / TERNARY_PEAK_TOPS, 4), "traffic": None},
+                "cpu_baseline": None, "extra": {**pk, "settle_ms": round(settle_ms, 1)}}
+        print(json.dumps(line))
+        return
+
     if args.workload in ("cfg3", "cfg5", "quantpack", "paper6"):
         side_workload(args, torch, fatnn, si, dev)
         return
+    extra = {}
     if args.workload == "cfg2":
         case = si.cfg2()
         Lw, Lx = case.make()
@@ -494,10 +681,10 @@ def main():
             fatnn.ternary_gemm(Wp, Ap, case.M, case.N, case.K, case.act_mode, out=C)
 
         ops_per_step = 2.0 * case.macs()
-        config = {"workload": "cfg4: ternary GEMM M=N=K=8192, symmetric activations, int32 output; "
-                              "step = pack activations + GEMM",
+        config = {"workload": "cfg4: ternary GEMM M=N=K=8192 on the seeded operands (weights P(0)=0.33, activations "
+                              "uniform over 3 levels), symmetric activations, int32 output; step = pack activations + GEMM",
                   "M": case.M, "N": case.N, "K": case.K}
-        dominant = "plane_gemm_kernel (ternary GEMM)"
+        dominant = "plane_gemm_kernel (ternary GEMM, 128x128 tiles)"
 
     def step():
         pack_step()
@@ -527,16 +714,20 @@ def main():
         main_fn = L.fatnn_ternary_gemm
     hook_fn = L.fatnn_time_next_launch
 
-    # ---- warm-up, then exactly K timed steps ------------------------------------------------
+    # ---- untimed: let the clocks settle, measure the ceilings on this GPU, warm up -------------
+    settle_ms = settle_clocks(torch, step)
+    peaks = measure_peaks(torch, fatnn)
+    settle_ms += settle_clocks(torch, step, 0.1)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # Timed launches of the dominant kernel carry a pair of HIP events attached to their
-    # dispatch (on the stream it is launched on), so its duration is measured inside the timed
-    # region without serialising anything.
-    # Attaching an event pair to a dispatch costs about 5 us of step time with this runtime (measured: 27 vs 22 us
-    # per step), so every EVENT_EVERY-th timed step carries one, not every step.
-    EVENT_EVERY = 8 if args.steps >= 32 else 1
+    # ---- exactly K timed steps ----------------------------------------------------------------
+    # Timed launches of the dominant kernel carry a pair of HIP events attached to their dispatch
+    # (on the stream it is launched on), so its duration is measured inside the timed region
+    # without serialising anything.  Attaching a pair costs about 5 us of step time with this
+    # runtime: nothing against a millisecond GEMM, a quarter of a 20 us convolution step, so the
+    # short workload carries one on every 8th step only.
+    EVENT_EVERY = 8 if (args.workload == "cfg2" and args.steps >= 32) else 1
     timed = list(range(0, args.steps, EVENT_EVERY))
     hev = HipEvents(2 * len(timed))
     handles = {i: (vp(hev.handle(2 * j)), vp(hev.handle(2 * j + 1))) for j, i in enumerate(timed)}
@@ -558,10 +749,9 @@ def main():
     value = ops_per_step / (ms_per_step * 1e-3) / 1e12
 
     achieved = ops_per_step / (kernel_ms * 1e-3) / 1e12
-    roofline = {"bound": "alu", "kernel": dominant, "achieved": round(achieved, 2),
-                "peak": round(TERNARY_PEAK_TOPS, 1), "unit": "Tops/s", "frac": round(achieved / TERNARY_PEAK_TOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel_ms": round(kernel_ms, 5),
-                "peak_basis": "256 CU x 64 lanes x 2.4 GHz = 39.3 T lane-instr/s; 4 lane-instr per 64 ops"}
+    roofline = alu_roofline(dominant, achieved, kernel_ms, peaks, measured_traffic_bytes(args.workload))
+    extra["settle_ms_untimed"] = round(settle_ms, 1)
+    extra["peaks_measured_in_this_run"] = peaks
 
     # ---- side measurements (outside the timed region) ---------------------------------------
     if not args.no_extra:
@@ -588,28 +778,6 @@ def main():
                 # Table 4's ablation: the same layer with the xnor rule alone (no zero-operand fix)
                 extra["xnor_only_conv_ms"] = round(t4, 5)
                 extra["extra_bit_ops_cost"] = round((t3 - t4) / t3, 4)
-                # the large-GEMM roofline point
-                g = si.cfg4()
-                Gw = torch.randint(0, 3, (g.M, g.K), dtype=torch.int8, device=dev)
-                Ga = torch.randint(0, 3, (g.N, g.K), dtype=torch.int8, device=dev)
-                Gwp = fatnn.pack_ternary(Gw, fatnn.WEIGHT)
-                Gap = fatnn.pack_ternary(Ga, fatnn.ACT)
-                Gc = torch.empty((g.M, g.N), dtype=torch.int32, device=dev)
-                tg = time_kernel_ms(torch, lambda: fatnn.ternary_gemm(Gwp, Gap, g.M, g.N, g.K, 0, out=Gc), 10, 2)
-                G2w = fatnn.pack_twobit(code[Gw.long()])
-                G2a = fatnn.pack_twobit(code[Ga.long()])
-                tg2 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(G2w, G2a, g.M, g.N, g.K, 0, out=Gc), 10, 2)
-                tg3 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(G2w, G2a, g.M, g.N, g.K, 2, out=Gc), 10, 2)
-                Bw = fatnn.pack_binary(torch.randint(0, 2, (g.M, g.K), dtype=torch.int8, device=dev))
-                Ba = fatnn.pack_binary(torch.randint(0, 2, (g.N, g.K), dtype=torch.int8, device=dev))
-                tb = time_kernel_ms(torch, lambda: fatnn.binary_gemm(Bw, Ba, g.M, g.N, g.K, out=Gc), 10, 2)
-                gt = 2.0 * g.macs() / (tg * 1e-3) / 1e12
-                extra["gemm8192"] = {"ternary_ms": round(tg, 4), "ternary_tops": round(gt, 1),
-                                     "frac_of_alu_peak": round(gt / TERNARY_PEAK_TOPS, 4),
-                                     "twobit_ms": round(tg2, 4), "speedup_vs_twobit": round(tg2 / tg, 3),
-                                     "binary_ms": round(tb, 4), "ternary_over_binary": round(tg / tb, 3),
-                                     "xnor_only_ms": round(tg3, 4), "extra_bit_ops_cost": round((tg - tg3) / tg, 4)}
-                del Gw, Ga, Gwp, Gap, Gc, G2w, G2a, Bw, Ba
                 # int8 MFMA comparison point (context only): same operands as int8 values through the BLAS
                 try:
                     a8 = (Lw_d.reshape(case.Cout, -1) - 1).contiguous()
@@ -619,18 +787,31 @@ def main():
                 except Exception as exc:       # comparison only; never fatal
                     extra["int8_mfma_gemm_same_shape_ms"] = f"unavailable: {type(exc).__name__}"
             else:
+                tk = extra["main_kernel_ms_back_to_back"]
                 W2 = fatnn.pack_twobit(code[Lw_d.long()])
                 A2 = fatnn.pack_twobit(code[La_d.long()])
                 t2 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(W2, A2, case.M, case.N, case.K, 0, out=C), 10, 2)
+                t3 = time_kernel_ms(torch, lambda: fatnn.twobit_gemm(W2, A2, case.M, case.N, case.K, 2, out=C), 10, 2)
                 extra["twobit_gemm_ms"] = round(t2, 4)
-                extra["speedup_vs_twobit"] = round(t2 / extra["main_kernel_ms_back_to_back"], 3)
+                extra["speedup_vs_twobit"] = round(t2 / tk, 3)
+                extra["xnor_only_gemm_ms"] = round(t3, 4)
+                extra["extra_bit_ops_cost"] = round((tk - t3) / tk, 4)
+                del W2, A2
+                Bw = fatnn.pack_binary((Lw_d == 2).to(torch.int8))
+                Ba = fatnn.pack_binary((La_d == 2).to(torch.int8))
+                tb = time_kernel_ms(torch, lambda: fatnn.binary_gemm(Bw, Ba, case.M, case.N, case.K, out=C), 10, 2)
+                extra["binary_gemm_ms"] = round(tb, 4)
+                extra["ternary_over_binary"] = round(tk / tb, 3)
+                del Bw, Ba
                 try:
                     a8 = (Lw_d - 1).contiguous()
                     x8 = (La_d - 1).t().contiguous()
                     ti = time_kernel_ms(torch, lambda: torch._int_mm(a8, x8), 5, 2)
                     extra["int8_mfma_gemm_ms"] = round(ti, 4)
+                    del a8, x8
                 except Exception as exc:
                     extra["int8_mfma_gemm_ms"] = f"unavailable: {type(exc).__name__}"
+                extra["other_configs"] = other_config_summaries(torch, fatnn, si, dev, peaks)
         except Exception as exc:   # side measurements must never lose the main line
             extra["error"] = f"{type(exc).__name__}: {exc}"
 

@@ -275,8 +275,32 @@ int fatnn_level_status(int64_t n_invalid_host);
 int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups);
 
 /*
+ * Roofline probes (no paper passage: they measure the denominators of the roofline report on the
+ * chip).  Both attach the events of fatnn_time_next_launch to their one kernel.
+ *
+ * fatnn_probe_valu issues, from registers only, the instruction pair that the reduced form of Eq. 3
+ * costs per 32-bit plane word (one three-input logic instruction feeding one accumulating popcount),
+ * with `waves_per_simd` wavefronts on every SIMD of the device.
+ *   kind            0 pair, all operands in vector registers (as the tiled GEMM kernel issues it)
+ *                   1 pair with the data word in a scalar register (as the streaming conv kernel does)
+ *                   2 popcount alone   3 logic instruction alone   4 plain two-input xor
+ *   waves_per_simd  1..8;  iters >= 1 loop iterations of 128 instructions each
+ *   scratch         device, 16-byte aligned, at least fatnn_probe_scratch_bytes() bytes; contents
+ *                   are read as operand values (any bit pattern) and overwritten
+ *   lane_instr      HOST pointer or NULL: receives the number of 32-bit lane-instructions the launch
+ *                   executes (workgroups * 256 lanes * iters * 128)
+ * fatnn_probe_hbm streams `bytes` (a multiple of 16) with 128-bit accesses: kind 0 reads src, 1 writes
+ * dst, 2 copies src to dst (bytes read + bytes written = 2 * bytes); the unused pointer may be NULL.
+ */
+size_t fatnn_probe_scratch_bytes(void);
+int fatnn_probe_valu(int kind, int waves_per_simd, int iters, void *scratch, size_t scratch_bytes,
+                     int64_t *lane_instr, void *stream);
+int fatnn_probe_hbm(int kind, void *dst, const void *src, size_t bytes, void *scratch, size_t scratch_bytes,
+                    void *stream);
+
+/*
  * Measurement hook (no paper passage: it serves the roofline report).  The next
- * fatnn_*_gemm / fatnn_*_conv2d call made by the calling thread attaches the two
+ * fatnn_*_gemm / fatnn_*_conv2d / fatnn_probe_* call made by the calling thread attaches the two
  * events to its kernel dispatch, so that hipEventElapsedTime(start, stop) is the
  * duration of that kernel alone, without the launch gap that events recorded around
  * the call would include.  Both are hipEvent_t created by the caller with timing

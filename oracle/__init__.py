@@ -46,6 +46,8 @@ def _load() -> ctypes.CDLL:
         lib.oracle_binary_gemm.argtypes = [i8p, i8p, i64, i64, i64, i32p]
         lib.oracle_scale_epilogue.argtypes = [i32p, i64, i64, ctypes.c_int, fp, fp, fp]
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        lib.oracle_set_num_threads.restype = None
         _lib = lib
     return _lib
 
@@ -59,6 +61,11 @@ def _i8(a: np.ndarray) -> np.ndarray:
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads the C loops use from now on (timing only; results do not depend on it)."""
+    _load().oracle_set_num_threads(int(n))
 
 
 def ternary_gemm(Lw: np.ndarray, La: np.ndarray, act_mode: int = SYM) -> np.ndarray:

@@ -192,3 +192,13 @@ int oracle_num_threads(void) {
     return 1;
 #endif
 }
+
+/* Number of OpenMP threads the loops above use from now on (for timing the oracle on one core). */
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

@@ -25,7 +25,8 @@ EXPORTS = [
     "fatnn_quantize_pack_bordered", "fatnn_bordered_act_init", "fatnn_ternary_conv2d_chain",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
     "fatnn_twobit_conv2d", "fatnn_binary_packed_bytes", "fatnn_pack_binary", "fatnn_binary_gemm",
-    "fatnn_time_next_launch", "fatnn_set_tuning", "fatnn_level_status", "fatnn_status_str", "fatnn_version",
+    "fatnn_time_next_launch", "fatnn_set_tuning", "fatnn_level_status",
+    "fatnn_probe_scratch_bytes", "fatnn_probe_valu", "fatnn_probe_hbm", "fatnn_status_str", "fatnn_version",
 ]
 
 
@@ -81,6 +82,9 @@ def lib() -> ctypes.CDLL:
         l.fatnn_time_next_launch.argtypes = [vp, vp]
         l.fatnn_set_tuning.argtypes = [i32, i32, i32]
         l.fatnn_level_status.argtypes = [i64]
+        l.fatnn_probe_scratch_bytes.restype = sz
+        l.fatnn_probe_valu.argtypes = [i32, i32, i32, vp, sz, ctypes.POINTER(i64), vp]
+        l.fatnn_probe_hbm.argtypes = [i32, vp, vp, sz, vp, sz, vp]
         l.fatnn_status_str.argtypes = [i32]
         l.fatnn_status_str.restype = ctypes.c_char_p
         l.fatnn_version.restype = i32
@@ -144,6 +148,29 @@ def binary_gemm(Wb: torch.Tensor, Ab: torch.Tensor, M: int, N: int, K: int,
 def set_tuning(conv_kernel: int = -1, stream_wps: int = -1, seven_pixel_groups: int = -1) -> None:
     """fatnn_set_tuning: process-wide measurement switches; -1 keeps a value."""
     _check(lib().fatnn_set_tuning(conv_kernel, stream_wps, seven_pixel_groups), "fatnn_set_tuning")
+
+
+PROBE_PAIR_V, PROBE_PAIR_S, PROBE_BCNT, PROBE_BITOP3, PROBE_XOR = 0, 1, 2, 3, 4
+HBM_READ, HBM_WRITE, HBM_COPY = 0, 1, 2
+
+
+def probe_scratch(device="cuda") -> torch.Tensor:
+    """Scratch buffer the roofline probes need (its contents serve as operand bits)."""
+    return torch.empty(int(lib().fatnn_probe_scratch_bytes()), dtype=torch.uint8, device=device).fill_(0x5A)
+
+
+def probe_valu(kind: int, waves_per_simd: int, iters: int, scratch: torch.Tensor) -> int:
+    """fatnn_probe_valu; returns the number of 32-bit lane-instructions the launch executes."""
+    n = ctypes.c_int64(0)
+    _check(lib().fatnn_probe_valu(kind, waves_per_simd, iters, _ptr(scratch), scratch.numel(), ctypes.byref(n),
+                                  _stream()), "fatnn_probe_valu")
+    return int(n.value)
+
+
+def probe_hbm(kind: int, dst: Optional[torch.Tensor], src: Optional[torch.Tensor], nbytes: int,
+              scratch: torch.Tensor) -> None:
+    _check(lib().fatnn_probe_hbm(kind, _ptr(dst), _ptr(src), nbytes, _ptr(scratch), scratch.numel(), _stream()),
+           "fatnn_probe_hbm")
 
 
 class _LevelCheck:

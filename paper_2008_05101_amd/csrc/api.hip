@@ -632,6 +632,59 @@ int fatnn_twobit_conv2d(const void* Wp, const void* Xp, int x_layout, int64_t B,
                     nullptr, stream);
 }
 
+// seed words + one result word per thread of the largest probe grid (8 wavefronts per SIMD on up to 1024 CUs)
+static constexpr size_t kProbeSeedBytes = 4096;
+static constexpr int kProbeMaxCUs = 1024;
+size_t fatnn_probe_scratch_bytes(void) { return kProbeSeedBytes + (size_t)kProbeMaxCUs * 8 * 256 * 4; }
+
+static int probe_cu_count(int* cus) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return FATNN_ERR_HIP;
+    if (prop.multiProcessorCount < 1 || prop.multiProcessorCount > kProbeMaxCUs) return FATNN_ERR_UNSUPPORTED;
+    *cus = prop.multiProcessorCount;
+    return FATNN_OK;
+}
+
+int fatnn_probe_valu(int kind, int waves_per_simd, int iters, void* scratch, size_t scratch_bytes,
+                     int64_t* lane_instr, void* stream) {
+    if (kind < 0 || kind > 4) return FATNN_ERR_UNSUPPORTED;
+    if (waves_per_simd < 1 || waves_per_simd > 8 || iters < 1) return FATNN_ERR_SHAPE;
+    if (scratch == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(scratch, 16)) return FATNN_ERR_ALIGN;
+    if (scratch_bytes < fatnn_probe_scratch_bytes()) return FATNN_ERR_SIZE;
+    int cus = 0;
+    const int rc = probe_cu_count(&cus);
+    if (rc != FATNN_OK) return rc;
+    // one workgroup = four wavefronts = one per SIMD of the CU it lands on
+    const int blocks = cus * waves_per_simd;
+    if (lane_instr != nullptr)
+        *lane_instr = (int64_t)blocks * 256 * iters * probe_pairs_per_iteration() * 2;
+    char* base = reinterpret_cast<char*>(scratch);
+    return launch_valu_probe(kind, blocks, iters, reinterpret_cast<const uint32_t*>(base),
+                             reinterpret_cast<int32_t*>(base + kProbeSeedBytes),
+                             reinterpret_cast<hipStream_t>(stream)) == 0
+               ? FATNN_OK
+               : FATNN_ERR_HIP;
+}
+
+int fatnn_probe_hbm(int kind, void* dst, const void* src, size_t bytes, void* scratch, size_t scratch_bytes,
+                    void* stream) {
+    if (kind < 0 || kind > 2) return FATNN_ERR_UNSUPPORTED;
+    if (bytes == 0 || bytes % 16 != 0) return FATNN_ERR_SHAPE;
+    if ((kind != 1 && src == nullptr) || (kind != 0 && dst == nullptr) || scratch == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(dst, 16) || !aligned(scratch, 16)) return FATNN_ERR_ALIGN;
+    if (scratch_bytes < fatnn_probe_scratch_bytes()) return FATNN_ERR_SIZE;
+    int cus = 0;
+    const int rc = probe_cu_count(&cus);
+    if (rc != FATNN_OK) return rc;
+    return launch_hbm_probe(kind, dst, src, bytes, cus * 8,
+                            reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(scratch) + kProbeSeedBytes),
+                            reinterpret_cast<hipStream_t>(stream)) == 0
+               ? FATNN_OK
+               : FATNN_ERR_HIP;
+}
+
 int fatnn_level_status(int64_t n_invalid_host) { return n_invalid_host == 0 ? FATNN_OK : FATNN_ERR_LEVEL; }
 
 int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups) {

@@ -135,6 +135,15 @@ bool stream_supported(int op, int R, int S, int Cw, int stride);
 int launch_stream_conv(const StreamParams& p, int op, int R, int Cw, int stride, int64_t out_rows, int64_t Wo,
                        hipStream_t stream);
 
+// Roofline probes (peaks.hip): register-resident issue-rate loop of the method's instruction pair and
+// HBM streaming passes.  kind of the VALU probe: 0 pair with vector operands, 1 pair with the data word in
+// an SGPR, 2 popcount alone, 3 three-input logic alone, 4 plain xor.  kind of the HBM probe: 0 read, 1 write,
+// 2 copy.  Both consume the launch-timing hook.
+int probe_pairs_per_iteration();
+int launch_valu_probe(int kind, int blocks, int iters, const uint32_t* seed, int32_t* sink, hipStream_t stream);
+int launch_hbm_probe(int kind, void* dst, const void* src, size_t bytes, int blocks, uint32_t* sink,
+                     hipStream_t stream);
+
 // Bordered activation packing: levels NHWC [B][H][W][C] -> [B][H+2*border][W+2*border][C/32]
 // word pairs, ring pixels = border_word; `slack_pixels` more pixels of border_word follow.
 int launch_pack_bordered(const int8_t* levels, int64_t B, int64_t H, int64_t W, int64_t C, int border, int kind,

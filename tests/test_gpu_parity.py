@@ -419,27 +419,31 @@ def test_conv_cfg3_layers_batch4(layer, bordered):
     assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode))
 
 
-def test_conv_cfg3_full_batch_sampled_images():
-    # full launch configuration (batch 64); the oracle recomputes four whole images of three layers
-    for layer in (0, 9, 15):
-        case = si.cfg3(batch=64)[layer]
-        Lw, Lx = case.make()
-        Y, _ = conv_gpu(Lw, Lx, case.stride, case.pad, case.act_mode)
-        Y = Y.cpu().numpy()
-        for b in (0, 21, 42, 63):
-            want = oracle.ternary_conv2d(Lw, Lx[b:b + 1], case.stride, case.pad, case.act_mode)
-            assert np.array_equal(Y[b:b + 1], want), (layer, b)
+@pytest.mark.parametrize("layer", range(19))
+def test_conv_cfg3_layers_batch64_every_element(layer):
+    # the launch configuration bench.py times: batch 64, bordered input, every output of every layer
+    case = si.cfg3(batch=64)[layer]
+    Lw, Lx = case.make()
+    Y, _ = conv_gpu(Lw, Lx, case.stride, case.pad, case.act_mode)
+    assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode))
+
+
+@pytest.mark.parametrize("layer", [1, 6, 12, 17])
+def test_conv_cfg3_layers_batch64_tiled_kernel_every_element(layer):
+    # the same through the LDS-tiled kernel's implicit-im2col front end (plain packed input)
+    case = si.cfg3(batch=64)[layer]
+    Lw, Lx = case.make()
+    Y, _ = conv_gpu(Lw, Lx, case.stride, case.pad, case.act_mode, bordered=False)
+    assert np.array_equal(Y.cpu().numpy(), oracle.ternary_conv2d(Lw, Lx, case.stride, case.pad, case.act_mode))
 
 
 @pytest.mark.parametrize("idx", [0, 1])
-def test_conv_cfg5_bottleneck_1x1_full(idx):
+def test_conv_cfg5_bottleneck_1x1_every_image(idx):
     case = si.cfg5_bottleneck()[idx]
     Lw, Lx = case.make()
     Y, _ = conv_gpu(Lw, Lx, 1, 0, case.act_mode)
     Y = Y.cpu().numpy()
-    for b in (0, 63, 127):
-        want = oracle.ternary_conv2d(Lw, Lx[b:b + 1], 1, 0, case.act_mode)
-        assert np.array_equal(Y[b:b + 1], want)
+    assert np.array_equal(Y, oracle.ternary_conv2d(Lw, Lx, 1, 0, case.act_mode))
     # a 1x1 convolution is the GEMM over pixels
     C, _ = gemm_gpu(Lw.reshape(case.Cout, case.Cin), Lx[:2].reshape(-1, case.Cin), case.act_mode)
     assert np.array_equal(C.cpu().numpy().T, Y[:2].reshape(-1, case.Cout))
@@ -461,25 +465,18 @@ def test_gemv_cfg5_full():
         assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, mode))
 
 
-def test_gemm_cfg4_full_size_sampled_rows_and_columns():
+def test_gemm_cfg4_full_size_every_element():
+    # 8192^3 on the seeded operands bench.py times; the oracle needs a few tens of seconds for all
+    # 67 million outputs (it is cut into row blocks so that a progress line appears for each)
     case = si.cfg4()
     Lw, La = case.make()
     C, _ = gemm_gpu(Lw, La, 0)
     C = C.cpu().numpy()
-    rnd = np.random.default_rng(44)
-    rows = np.sort(rnd.choice(case.M, 48, replace=False))
-    rows[0], rows[-1] = 0, case.M - 1
-    assert np.array_equal(C[rows], oracle.ternary_gemm(Lw[rows], La, 0))
-    cols = np.sort(rnd.choice(case.N, 48, replace=False))
-    cols[0], cols[-1] = 0, case.N - 1
-    assert np.array_equal(C[:, cols], oracle.ternary_gemm(Lw, La[cols], 0))
-    # properties that hold at any size: parity of C and the magnitude bound
-    nzw = torch.from_numpy((Lw != 1).astype(np.float32)).to(DEV)
-    nza = torch.from_numpy((La != 1).astype(np.float32)).to(DEV)
-    both = (nzw @ nza.T).to(torch.int32)                  # exact in fp32: counts <= 8192
-    Cd = torch.from_numpy(C).to(DEV)
-    assert bool(((Cd & 1) == (both & 1)).all())
-    assert bool((Cd.abs() <= both).all())
+    step = 1024
+    for r0 in range(0, case.M, step):
+        want = oracle.ternary_gemm(np.ascontiguousarray(Lw[r0:r0 + step]), La, 0)
+        assert np.array_equal(C[r0:r0 + step], want), f"rows {r0}..{r0 + step - 1}"
+        print(f"cfg4 rows {r0}..{r0 + step - 1} equal", flush=True)
 
 
 # ----------------------------------------------------------------------------- conventional two-bit path
