@@ -258,6 +258,30 @@ int fatnn_pack_binary(const int8_t *bits, int64_t rows, int64_t K, void *packed,
 int fatnn_binary_gemm(const void *Wb, const void *Ab, int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
                       void *stream);
 
+/*
+ * The three GEMM calls above with a workspace, for problems whose tiles do not fill the 256 compute units
+ * evenly (a few hundred tiles, or few tiles with a long K: fully connected layers at batch 17-128, which
+ * Supplementary S1 treats as convolutions whose filter covers the whole feature map).  Same arguments,
+ * results identical bit for bit; with the workspace the library may cut the K loops of the tiles into
+ * equal shares for all workgroups and combine the partial popcount sums of Eq. 3 through it.
+ *   workspace        device, 16-byte aligned, or NULL (then exactly the plain call)
+ *   workspace_bytes  any size; fatnn_gemm_workspace_bytes() lets every shape use the full schedule, a
+ *                    smaller one limits the number of workgroups, one below 128 KiB is not used at all
+ * The first 64 KiB of the workspace (tile counters) must be zero before the first call;
+ * fatnn_gemm_workspace_init zeroes the whole workspace with a fill kernel, which is safe to capture into a
+ * HIP graph.  Every call leaves the counters zero again, so one initialisation serves any number of calls.
+ * Calls that share a workspace must be ordered (same stream, or events): they would race on it otherwise.
+ */
+size_t fatnn_gemm_workspace_bytes(void);
+int fatnn_gemm_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+int fatnn_ternary_gemm_ws(const void *Wp, const void *Ap, int64_t M, int64_t N, int64_t K, int act_mode,
+                          int32_t *C, int64_t ldc, const float *scale, const float *bias, float *Cf,
+                          int64_t ldcf, void *workspace, size_t workspace_bytes, void *stream);
+int fatnn_twobit_gemm_ws(const void *Wp, const void *Ap, int64_t M, int64_t N, int64_t K, int basis,
+                         int32_t *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream);
+int fatnn_binary_gemm_ws(const void *Wb, const void *Ab, int64_t M, int64_t N, int64_t K, int32_t *C,
+                         int64_t ldc, void *workspace, size_t workspace_bytes, void *stream);
+
 /* FATNN_OK for a zero count of out-of-set inputs, FATNN_ERR_LEVEL otherwise (first constraint of
  * Section 3.3).  `n_invalid_host` is the value of a packing call's counter copied to the host. */
 int fatnn_level_status(int64_t n_invalid_host);
@@ -270,9 +294,11 @@ int fatnn_level_status(int64_t n_invalid_host);
  *   conv_kernel         0 = automatic, 1 = convolutions always take the LDS-tiled kernel
  *   stream_wps          wavefronts per SIMD of the column-streaming kernel, 0 = planned, at most 8
  *   seven_pixel_groups  0 = off, 1 = by the size rule, 2 = wherever a kernel exists
+ *   gemm_even_share     schedule of the *_gemm_ws calls: 0 = automatic, 1..8 = even shares with that many
+ *                       workgroups per compute unit whatever the size, 9 = never
  * Results never depend on these, only the kernel and launch shape chosen.
  */
-int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups);
+int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups, int gemm_even_share);
 
 /*
  * Roofline probes (no paper passage: they measure the denominators of the roofline report on the

@@ -25,6 +25,8 @@ EXPORTS = [
     "fatnn_quantize_pack_bordered", "fatnn_bordered_act_init", "fatnn_ternary_conv2d_chain",
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
     "fatnn_twobit_conv2d", "fatnn_binary_packed_bytes", "fatnn_pack_binary", "fatnn_binary_gemm",
+    "fatnn_gemm_workspace_bytes", "fatnn_gemm_workspace_init", "fatnn_ternary_gemm_ws", "fatnn_twobit_gemm_ws",
+    "fatnn_binary_gemm_ws",
     "fatnn_time_next_launch", "fatnn_set_tuning", "fatnn_level_status",
     "fatnn_probe_scratch_bytes", "fatnn_probe_valu", "fatnn_probe_hbm", "fatnn_status_str", "fatnn_version",
 ]
@@ -80,7 +82,12 @@ def lib() -> ctypes.CDLL:
         l.fatnn_pack_binary.argtypes = [vp, i64, i64, vp, sz, vp, vp]
         l.fatnn_binary_gemm.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
         l.fatnn_time_next_launch.argtypes = [vp, vp]
-        l.fatnn_set_tuning.argtypes = [i32, i32, i32]
+        l.fatnn_set_tuning.argtypes = [i32, i32, i32, i32]
+        l.fatnn_gemm_workspace_bytes.restype = sz
+        l.fatnn_gemm_workspace_init.argtypes = [vp, sz, vp]
+        l.fatnn_ternary_gemm_ws.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, i64, vp, sz, vp]
+        l.fatnn_twobit_gemm_ws.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, sz, vp]
+        l.fatnn_binary_gemm_ws.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, sz, vp]
         l.fatnn_level_status.argtypes = [i64]
         l.fatnn_probe_scratch_bytes.restype = sz
         l.fatnn_probe_valu.argtypes = [i32, i32, i32, vp, sz, ctypes.POINTER(i64), vp]
@@ -136,18 +143,45 @@ def pack_binary(bits: torch.Tensor, out: Optional[torch.Tensor] = None,
 
 
 def binary_gemm(Wb: torch.Tensor, Ab: torch.Tensor, M: int, N: int, K: int,
-                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, workspace="auto") -> torch.Tensor:
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=Wb.device)
     ldc = out.stride(0) if out.dim() == 2 and M > 0 else N
-    _check(lib().fatnn_binary_gemm(_ptr(Wb), _ptr(Ab), M, N, K, _ptr(out), max(ldc, N), _stream()),
-           "fatnn_binary_gemm")
+    ws = _ws(workspace, Wb.device)
+    _check(lib().fatnn_binary_gemm_ws(_ptr(Wb), _ptr(Ab), M, N, K, _ptr(out), max(ldc, N), _ptr(ws),
+                                      0 if ws is None else ws.numel(), _stream()), "fatnn_binary_gemm_ws")
     return out
 
 
-def set_tuning(conv_kernel: int = -1, stream_wps: int = -1, seven_pixel_groups: int = -1) -> None:
+def set_tuning(conv_kernel: int = -1, stream_wps: int = -1, seven_pixel_groups: int = -1,
+               gemm_even_share: int = -1) -> None:
     """fatnn_set_tuning: process-wide measurement switches; -1 keeps a value."""
-    _check(lib().fatnn_set_tuning(conv_kernel, stream_wps, seven_pixel_groups), "fatnn_set_tuning")
+    _check(lib().fatnn_set_tuning(conv_kernel, stream_wps, seven_pixel_groups, gemm_even_share), "fatnn_set_tuning")
+
+
+_workspaces = {}
+
+
+def gemm_workspace(device, nbytes: Optional[int] = None) -> torch.Tensor:
+    """A workspace for the *_gemm_ws calls: allocated by torch and initialised once per device (or a fresh
+    one of `nbytes` bytes).  Calls that use the shared one must run on one stream at a time."""
+    dev = torch.device(device)
+    if dev.index is None:
+        dev = torch.device("cuda", torch.cuda.current_device())
+    if nbytes is None and dev in _workspaces:
+        return _workspaces[dev]
+    ws = torch.empty(int(lib().fatnn_gemm_workspace_bytes()) if nbytes is None else nbytes, dtype=torch.uint8, device=dev)
+    _check(lib().fatnn_gemm_workspace_init(_ptr(ws), ws.numel(), _stream()), "fatnn_gemm_workspace_init")
+    if nbytes is None:
+        _workspaces[dev] = ws
+    return ws
+
+
+def _ws(workspace, device) -> Optional[torch.Tensor]:
+    """workspace argument of the GEMM wrappers: "auto" = the device's shared one, None = none, or a tensor."""
+    if isinstance(workspace, str):
+        return gemm_workspace(device)
+    return workspace
 
 
 PROBE_PAIR_V, PROBE_PAIR_S, PROBE_BCNT, PROBE_BITOP3, PROBE_XOR = 0, 1, 2, 3, 4
@@ -357,16 +391,18 @@ def quantize_pack_bordered(x: torch.Tensor, border: int, act_mode: int, alpha1: 
 def ternary_gemm(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, act_mode: int = SYM,
                  out: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
                  bias: Optional[torch.Tensor] = None, out_f: Optional[torch.Tensor] = None,
-                 want_int: bool = True):
-    """fatnn_ternary_gemm.  Returns (C int32 [M][N] or None, Cf fp32 [M][N] or None)."""
+                 want_int: bool = True, workspace="auto"):
+    """fatnn_ternary_gemm_ws.  Returns (C int32 [M][N] or None, Cf fp32 [M][N] or None)."""
     if out is None and want_int:
         out = torch.empty((M, N), dtype=torch.int32, device=Wp.device)
     if scale is not None and out_f is None:
         out_f = torch.empty((M, N), dtype=torch.float32, device=Wp.device)
     ldc = out.stride(0) if out is not None and out.dim() == 2 and M > 0 else N
     ldcf = out_f.stride(0) if out_f is not None and out_f.dim() == 2 and M > 0 else N
-    _check(lib().fatnn_ternary_gemm(_ptr(Wp), _ptr(Ap), M, N, K, act_mode, _ptr(out), max(ldc, N), _ptr(scale),
-                                    _ptr(bias), _ptr(out_f), max(ldcf, N), _stream()), "fatnn_ternary_gemm")
+    ws = _ws(workspace, Wp.device)
+    _check(lib().fatnn_ternary_gemm_ws(_ptr(Wp), _ptr(Ap), M, N, K, act_mode, _ptr(out), max(ldc, N), _ptr(scale),
+                                       _ptr(bias), _ptr(out_f), max(ldcf, N), _ptr(ws),
+                                       0 if ws is None else ws.numel(), _stream()), "fatnn_ternary_gemm_ws")
     return out, out_f
 
 
@@ -416,12 +452,13 @@ def ternary_conv2d_chain(Wp: torch.Tensor, Xp: torch.Tensor, B: int, Cin: int, H
 
 
 def twobit_gemm(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, basis: int = BASIS_TERNARY,
-                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, workspace="auto") -> torch.Tensor:
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=Wp.device)
     ldc = out.stride(0) if out.dim() == 2 and M > 0 else N
-    _check(lib().fatnn_twobit_gemm(_ptr(Wp), _ptr(Ap), M, N, K, basis, _ptr(out), max(ldc, N), _stream()),
-           "fatnn_twobit_gemm")
+    ws = _ws(workspace, Wp.device)
+    _check(lib().fatnn_twobit_gemm_ws(_ptr(Wp), _ptr(Ap), M, N, K, basis, _ptr(out), max(ldc, N), _ptr(ws),
+                                      0 if ws is None else ws.numel(), _stream()), "fatnn_twobit_gemm_ws")
     return out
 
 

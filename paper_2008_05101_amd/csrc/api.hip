@@ -19,7 +19,7 @@ thread_local LaunchTiming g_timing = {nullptr, nullptr};
 // thread-safe); fatnn_set_tuning overwrites them; launches only read them.
 namespace {
 struct TuningState {
-    std::atomic<int> force_tiled, stream_wps, u7_mode;
+    std::atomic<int> force_tiled, stream_wps, u7_mode, gemm_even_share;
     TuningState() {
         const char* e = getenv("FATNN_CONV_KERNEL");
         force_tiled.store(e != nullptr && e[0] == 't' ? 1 : 0);
@@ -28,6 +28,8 @@ struct TuningState {
         stream_wps.store(w > 0 ? w : 0);
         e = getenv("FATNN_STREAM_U7");
         u7_mode.store((e != nullptr && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 1);
+        e = getenv("FATNN_GEMM_EVEN_SHARE");
+        gemm_even_share.store((e != nullptr && e[0] >= '0' && e[0] <= '9') ? e[0] - '0' : 0);
     }
 };
 TuningState& tuning_state() {
@@ -41,13 +43,15 @@ Tuning tuning() {
     v.force_tiled = s.force_tiled.load(std::memory_order_relaxed) != 0;
     v.stream_wps = s.stream_wps.load(std::memory_order_relaxed);
     v.u7_mode = s.u7_mode.load(std::memory_order_relaxed);
+    v.gemm_even_share = s.gemm_even_share.load(std::memory_order_relaxed);
     return v;
 }
-void set_tuning(int force_tiled, int stream_wps, int u7_mode) {
+void set_tuning(int force_tiled, int stream_wps, int u7_mode, int gemm_even_share) {
     TuningState& s = tuning_state();
     if (force_tiled >= 0) s.force_tiled.store(force_tiled != 0 ? 1 : 0, std::memory_order_relaxed);
     if (stream_wps >= 0) s.stream_wps.store(stream_wps, std::memory_order_relaxed);
     if (u7_mode >= 0) s.u7_mode.store(u7_mode, std::memory_order_relaxed);
+    if (gemm_even_share >= 0) s.gemm_even_share.store(gemm_even_share, std::memory_order_relaxed);
 }
 LaunchTiming take_launch_timing() {
     const LaunchTiming t = g_timing;
@@ -470,6 +474,12 @@ int fatnn_quantize_pack_bordered(const float* x, const int64_t dims[4], int bord
 int fatnn_ternary_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int act_mode,
                        int32_t* C, int64_t ldc, const float* scale, const float* bias, float* Cf,
                        int64_t ldcf, void* stream) {
+    return fatnn_ternary_gemm_ws(Wp, Ap, M, N, K, act_mode, C, ldc, scale, bias, Cf, ldcf, nullptr, 0, stream);
+}
+
+int fatnn_ternary_gemm_ws(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int act_mode,
+                          int32_t* C, int64_t ldc, const float* scale, const float* bias, float* Cf,
+                          int64_t ldcf, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_gemm_dims(M, N, K);
     if (rc != FATNN_OK) return rc;
     if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
@@ -480,9 +490,11 @@ int fatnn_ternary_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int
     if (Cf != nullptr && ldcf < N) return FATNN_ERR_SHAPE;
     if (Wp == nullptr || Ap == nullptr) return FATNN_ERR_NULL;
     if (!aligned(Wp, 16) || !aligned(Ap, 16) || !aligned(C, 4) || !aligned(Cf, 4) || !aligned(scale, 4) ||
-        !aligned(bias, 4))
+        !aligned(bias, 4) || !aligned(workspace, 16))
         return FATNN_ERR_ALIGN;
     GemmParams p{};
+    p.ws = workspace;
+    p.ws_bytes = workspace != nullptr ? workspace_bytes : 0;
     p.W = reinterpret_cast<const plane2*>(Wp);
     p.A = reinterpret_cast<const plane2*>(Ap);
     set_ternary_consts(p, Wp, M, K, act_mode);
@@ -589,6 +601,11 @@ int fatnn_ternary_conv2d_chain(const void* Wp, const void* Xp, int x_layout, int
 
 int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int basis, int32_t* C,
                       int64_t ldc, void* stream) {
+    return fatnn_twobit_gemm_ws(Wp, Ap, M, N, K, basis, C, ldc, nullptr, 0, stream);
+}
+
+int fatnn_twobit_gemm_ws(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int basis, int32_t* C,
+                         int64_t ldc, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_gemm_dims(M, N, K);
     if (rc != FATNN_OK) return rc;
     if (basis != FATNN_BASIS_TERNARY && basis != FATNN_BASIS_UNIFORM && basis != FATNN_BASIS_XNOR_ONLY)
@@ -598,8 +615,10 @@ int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int6
     if (C == nullptr) return FATNN_ERR_NULL;
     if (ldc < N) return FATNN_ERR_SHAPE;
     if (Wp == nullptr || Ap == nullptr) return FATNN_ERR_NULL;
-    if (!aligned(Wp, 16) || !aligned(Ap, 16) || !aligned(C, 4)) return FATNN_ERR_ALIGN;
+    if (!aligned(Wp, 16) || !aligned(Ap, 16) || !aligned(C, 4) || !aligned(workspace, 16)) return FATNN_ERR_ALIGN;
     GemmParams p{};
+    p.ws = workspace;
+    p.ws_bytes = workspace != nullptr ? workspace_bytes : 0;
     p.W = reinterpret_cast<const plane2*>(Wp);
     p.A = reinterpret_cast<const plane2*>(Ap);
     p.K = (int32_t)K;
@@ -687,9 +706,9 @@ int fatnn_probe_hbm(int kind, void* dst, const void* src, size_t bytes, void* sc
 
 int fatnn_level_status(int64_t n_invalid_host) { return n_invalid_host == 0 ? FATNN_OK : FATNN_ERR_LEVEL; }
 
-int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups) {
-    if (conv_kernel > 1 || stream_wps > 8 || seven_pixel_groups > 2) return FATNN_ERR_UNSUPPORTED;
-    fatnn::set_tuning(conv_kernel, stream_wps, seven_pixel_groups);
+int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups, int gemm_even_share) {
+    if (conv_kernel > 1 || stream_wps > 8 || seven_pixel_groups > 2 || gemm_even_share > 9) return FATNN_ERR_UNSUPPORTED;
+    fatnn::set_tuning(conv_kernel, stream_wps, seven_pixel_groups, gemm_even_share);
     return FATNN_OK;
 }
 
@@ -721,13 +740,39 @@ size_t fatnn_binary_packed_bytes(int64_t rows, int64_t K) {
 
 int fatnn_binary_gemm(const void* Wb, const void* Ab, int64_t M, int64_t N, int64_t K, int32_t* C, int64_t ldc,
                       void* stream) {
+    return fatnn_binary_gemm_ws(Wb, Ab, M, N, K, C, ldc, nullptr, 0, stream);
+}
+
+size_t fatnn_gemm_workspace_bytes(void) {
+    // tile counters + two hand-over slots for each of 4 workgroups per compute unit on 256 compute units,
+    // sized for the largest tile accumulator set (64 x 32 outputs of three words in the uniform two-bit basis)
+    return (size_t)kEvenShareCounterBytes + (size_t)1024 * 2 * (64 * 32 * 3 * 4);
+}
+
+int fatnn_gemm_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (workspace == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(workspace, 16)) return FATNN_ERR_ALIGN;
+    if (workspace_bytes < (size_t)kEvenShareCounterBytes) return FATNN_ERR_SIZE;
+    plane2 zero;
+    zero.x = 0u;
+    zero.y = 0u;
+    return launch_fill_words(reinterpret_cast<plane2*>(workspace), (int64_t)(workspace_bytes / sizeof(plane2)),
+                             zero, reinterpret_cast<hipStream_t>(stream)) == 0
+               ? FATNN_OK
+               : FATNN_ERR_HIP;
+}
+
+int fatnn_binary_gemm_ws(const void* Wb, const void* Ab, int64_t M, int64_t N, int64_t K, int32_t* C, int64_t ldc,
+                         void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || N < 0 || K < 1) return FATNN_ERR_SHAPE;
     if (M > kMaxRows || N > kMaxRows || K > 2 * (int64_t)FATNN_MAX_K) return FATNN_ERR_SIZE;
     if (M == 0 || N == 0) return FATNN_OK;
     if (C == nullptr || Wb == nullptr || Ab == nullptr) return FATNN_ERR_NULL;
     if (ldc < N) return FATNN_ERR_SHAPE;
-    if (!aligned(Wb, 16) || !aligned(Ab, 16) || !aligned(C, 4)) return FATNN_ERR_ALIGN;
+    if (!aligned(Wb, 16) || !aligned(Ab, 16) || !aligned(C, 4) || !aligned(workspace, 16)) return FATNN_ERR_ALIGN;
     GemmParams p{};
+    p.ws = workspace;
+    p.ws_bytes = workspace != nullptr ? workspace_bytes : 0;
     p.W = reinterpret_cast<const plane2*>(Wb);
     p.A = reinterpret_cast<const plane2*>(Ab);
     p.K = (int32_t)K;

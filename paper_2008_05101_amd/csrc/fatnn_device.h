@@ -77,9 +77,19 @@ struct GemmParams {
     int32_t is_conv;
     int32_t B, H, Wd, Cw, Ho, Wo, R, S, stride, pad;
     uint32_t pad_x, pad_y;  // plane words of a padded tap (value 0)
+    // even-share schedule (GEMM only): device workspace whose first kEvenShareCounterBytes are zero, or null
+    void* ws;
+    size_t ws_bytes;
 };
 
+// Workspace of the even-share GEMM schedule: tile counters (one int32 per 64 x 64 tile, at most 16384 tiles)
+// followed by the hand-over slots.
+constexpr int64_t kEvenShareCounterBytes = 64 * 1024;
+
 int launch_gemm(const GemmParams& p, int op, hipStream_t stream);
+// The ternary GEMM under the even-share schedule whatever its size, wgs_per_cu workgroups per compute unit
+// (fewer if the workspace in p is smaller).  Returns 1 if the workspace cannot serve the problem.
+int launch_ternary_gemm_even_share(const GemmParams& p, int wgs_per_cu, hipStream_t stream);
 bool skinny_supported(const GemmParams& p, int op);          // N <= 8 ternary GEMM (matrix-vector shaped)
 int launch_skinny_gemm(const GemmParams& p, hipStream_t stream);
 
@@ -96,9 +106,11 @@ struct Tuning {
     bool force_tiled;   // convolutions go to the LDS-tiled kernel even where the streaming one applies
     int stream_wps;     // wavefronts per SIMD of the streaming kernel (0 = planned)
     int u7_mode;        // seven-pixel groups: 0 off, 1 by the size rule, 2 wherever a kernel exists
+    int gemm_even_share;  // even-share GEMM schedule: 0 automatic, 1..8 workgroups per CU forced, 9 never
 };
 Tuning tuning();
-void set_tuning(int force_tiled, int stream_wps, int u7_mode);   // a negative value keeps the current one
+// a negative value keeps the current one
+void set_tuning(int force_tiled, int stream_wps, int u7_mode, int gemm_even_share);
 
 // Column-streaming convolution (weights resident in registers, activations through
 // the scalar cache).  Input: bordered packed activations [B][Hp][Wp][Cw] (+ slack),

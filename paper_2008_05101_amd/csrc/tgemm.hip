@@ -23,6 +23,7 @@
 // eight lanes of a group.
 #include "fatnn_device.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace fatnn {
@@ -43,7 +44,9 @@ struct Acc;
 
 template <>
 struct Acc<OP_TERNARY> {
+    static constexpr int kWords = 1;
     int32_t v;
+    __device__ __forceinline__ int32_t& word(int) { return v; }
     __device__ __forceinline__ void clear() { v = 0; }
     __device__ __forceinline__ void step(plane2 w, plane2 a) {
         popc_acc(v, (a.x ^ w.x) & w.y);
@@ -53,7 +56,9 @@ struct Acc<OP_TERNARY> {
 
 template <>
 struct Acc<OP_TWOBIT_TERNARY> {
+    static constexpr int kWords = 1;
     int32_t v;
+    __device__ __forceinline__ int32_t& word(int) { return v; }
     __device__ __forceinline__ void clear() { v = 0; }
     __device__ __forceinline__ void step(plane2 w, plane2 a) {
         popc_acc(v, a.x ^ w.x);
@@ -65,7 +70,9 @@ struct Acc<OP_TWOBIT_TERNARY> {
 
 template <>
 struct Acc<OP_TWOBIT_UNIFORM> {
+    static constexpr int kWords = 3;
     int32_t s00, s01, s11;   // by weight of the plane pair: 1, 2, 4
+    __device__ __forceinline__ int32_t& word(int i) { return i == 0 ? s00 : (i == 1 ? s01 : s11); }
     __device__ __forceinline__ void clear() { s00 = s01 = s11 = 0; }
     __device__ __forceinline__ void step(plane2 w, plane2 a) {
         popc_acc(s00, a.y ^ w.y);
@@ -79,7 +86,9 @@ struct Acc<OP_TWOBIT_UNIFORM> {
 // elements per pair), and the xnor rule of Eq. 4 without the zero-operand fix of Eq. 5-7.
 template <>
 struct Acc<OP_XOR_PAIR> {
+    static constexpr int kWords = 1;
     int32_t v;
+    __device__ __forceinline__ int32_t& word(int) { return v; }
     __device__ __forceinline__ void clear() { v = 0; }
     __device__ __forceinline__ void step(plane2 w, plane2 a) {
         popc_acc(v, a.x ^ w.x);
@@ -114,9 +123,24 @@ __device__ __forceinline__ int32_t finalize<OP_TWOBIT_UNIFORM>(const Acc<OP_TWOB
     return 9 * p.K - 2 * acc.s00 - 4 * acc.s01 - 8 * acc.s11;
 }
 
-template <int OP, int WM, int WN, int TM, int TN, bool CONV>
+// Even-share ("stream-K") schedule.  The work of a GEMM is cut into units of one K stage (KT k-words) of
+// one output tile, numbered tile by tile; workgroup g of G owns the units [g*U/G, (g+1)*U/G), i.e. a run of
+// whole tiles with possibly a piece of a tile at either end.  Every workgroup therefore does the same
+// amount of arithmetic whatever the number of tiles is -- there is no last, partly filled round of tiles
+// on the 256 compute units.  A piece hands its partial popcount sums over through `partial` (one slot per
+// workgroup and end) and adds the number of its stages to the tile's counter; the piece whose addition
+// completes the count collects the other slots and runs the epilogue, so nobody ever waits for anybody.
+// The counters must be zero at launch and are zero again when the kernel has finished.
+struct StreamKArgs {
+    int32_t* partial;    // [G][2][tile accumulator words], written and read inside one launch
+    int32_t* counters;   // [ntiles]
+    int32_t nst;         // K stages per tile
+    int32_t units;       // ntiles * nst
+};
+
+template <int OP, int WM, int WN, int TM, int TN, bool CONV, bool STREAMK>
 __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
-                                                                        const int ntiles) {
+                                                                        const int ntiles, const StreamKArgs sk) {
     constexpr int NT = 64 * WM * WN;
     constexpr int BM = WM * 8 * TM;
     constexpr int BN = WN * 8 * TN;
@@ -125,30 +149,21 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
     static_assert((BM * KT) % NT == 0 && (BN * KT) % NT == 0, "tile does not divide over the threads");
     static_assert(TM % 2 == 0 && TN % 2 == 0, "lanes own row pairs");
     static_assert(NT % KT == 0, "a thread keeps one k-word slot");
+    static_assert(!(STREAMK && CONV), "the even-share schedule is built for the GEMM addressing only");
     constexpr int ROWS_PER_PASS = NT / KT;
     constexpr int PW = BM + LDS_PAD;
     constexpr int PA = BN + LDS_PAD;
 
     __shared__ __attribute__((aligned(16))) plane2 Ws[2][KT][PW];
     __shared__ __attribute__((aligned(16))) plane2 As[2][KT][PA];
+    __shared__ int32_t ticket;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
-    // logical tiles, and order the logical tiles in bands of kBand tile rows walked column by
-    // column, so that the ~64 tiles resident on one XCD at a time form a roughly square block
-    // (8 weight panels x 8 activation panels) and share their operand panels in that XCD's L2.
-    constexpr int kBand = 8;
+    // logical indices (gridDim.x is a multiple of 8).
     const int per_xcd = gridDim.x >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= ntiles) return;
+    if (!STREAMK && logical >= ntiles) return;
     const int tiles_n = ntiles / tiles_m;
-    const int band = logical / (kBand * tiles_n);
-    const int band_m0 = band * kBand;
-    const int band_rows = (tiles_m - band_m0) < kBand ? (tiles_m - band_m0) : kBand;
-    const int in_band = logical - band * kBand * tiles_n;
-    const int tile_m = band_m0 + in_band % band_rows;
-    const int tile_n = in_band / band_rows;
-    const int row0 = tile_m * BM;
-    const int col0 = tile_n * BN;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -161,187 +176,226 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
     const int ld_j = tid % KT;
     const int ld_r = tid / KT;
 
-    // ---- global addressing of the staged loads ------------------------------------------
-    // Both operands are read through buffer resources: a load whose byte offset is at or
-    // beyond num_records returns zero, which takes care of rows past M / N without any
-    // branch; k-words past the end of a row are sent to kOutOfRange on purpose.
-    constexpr uint32_t kOutOfRange = 0x80000000u;
-    constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
-    const int64_t wbase = (int64_t)row0 * p.Kw;
-    const int64_t wleft = ((int64_t)p.M * p.Kw - wbase) * (int64_t)sizeof(plane2);
-    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<plane2*>(p.W + wbase), 0, (int)(wleft < 0x7FFFFFFFLL ? wleft : 0x7FFFFFFFLL), kRsrcFlags);
-    uint32_t woff[LW];
-#pragma unroll
-    for (int i = 0; i < LW; ++i) woff[i] = (uint32_t)(ld_r + i * ROWS_PER_PASS) * (uint32_t)p.Kw * 8u;
-
-    int64_t abase, aleft;
-    uint32_t aoff[LA];   // GEMM: byte offset of the row.  conv: byte offset of the column's image
-    int hi0[LA], wi0[LA];
-    if (CONV) {
-        const int64_t img = (int64_t)p.H * p.Wd * p.Cw;          // word pairs per image
-        const int b0 = col0 / (p.Ho * p.Wo);
-        abase = (int64_t)b0 * img;
-        aleft = ((int64_t)p.B * img - abase) * (int64_t)sizeof(plane2);
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int n = col0 + ld_r + i * ROWS_PER_PASS;
-            const int nn = n < p.N ? n : col0;   // columns past N are never stored; keep them in range
-            const int wo = nn % p.Wo;
-            const int t = nn / p.Wo;
-            const int ho = t % p.Ho;
-            const int b = t / p.Ho;
-            hi0[i] = ho * p.stride - p.pad;
-            wi0[i] = wo * p.stride - p.pad;
-            aoff[i] = (uint32_t)(b - b0) * (uint32_t)img * 8u;
-        }
-    } else {
-        abase = (int64_t)col0 * p.Kw;
-        aleft = ((int64_t)p.N * p.Kw - abase) * (int64_t)sizeof(plane2);
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            hi0[i] = wi0[i] = 0;
-            aoff[i] = (uint32_t)(ld_r + i * ROWS_PER_PASS) * (uint32_t)p.Kw * 8u;
-        }
-    }
-    const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<plane2*>(p.A + abase), 0, (int)(aleft < 0x7FFFFFFFLL ? aleft : 0x7FFFFFFFLL), kRsrcFlags);
-
-    auto load2 = [](const __amdgpu_buffer_rsrc_t& r, uint32_t off) {
-        const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
-        plane2 o;
-        o.x = v[0];
-        o.y = v[1];
-        return o;
-    };
-
-    // Small tiles finish a stage faster than a global load returns, so they keep two stages in
-    // flight (two register sets); the large tiles have no registers to spare for that.
-    constexpr bool kTwoAhead = (LW + LA) <= 4;
-    constexpr int NSETS = kTwoAhead ? 2 : 1;
-    plane2 wregs[NSETS][LW], aregs[NSETS][LA];
-    auto fetch = [&](int kt, auto set_tag) {
-        constexpr int set = decltype(set_tag)::value;
-        plane2(&wreg)[LW] = wregs[set];
-        plane2(&areg)[LA] = aregs[set];
-        const int kw = kt * KT + ld_j;
-        const bool kok = kw < p.Kw;
-#pragma unroll
-        for (int i = 0; i < LW; ++i) wreg[i] = load2(wrsrc, kok ? woff[i] + (uint32_t)kw * 8u : kOutOfRange);
-        if (CONV) {
-            // k-word -> (filter tap, channel word); c is innermost in K
-            const int kwc = kok ? kw : 0;
-            const int tap = kwc / p.Cw;
-            const int cw = kwc - tap * p.Cw;
-            const int r = tap / p.S;
-            const int s = tap - r * p.S;
-#pragma unroll
-            for (int i = 0; i < LA; ++i) {
-                const int hi = hi0[i] + r;
-                const int wi = wi0[i] + s;
-                const bool inside = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd;
-                const uint32_t off = aoff[i] + (uint32_t)((hi * p.Wd + wi) * p.Cw + cw) * 8u;
-                plane2 v = load2(arsrc, (kok && inside) ? off : kOutOfRange);
-                // a padded tap is the value 0; only its low plane can be non-zero (codec 01)
-                v.y |= (kok && !inside) ? p.pad_y : 0u;
-                areg[i] = v;
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < LA; ++i) areg[i] = load2(arsrc, kok ? aoff[i] + (uint32_t)kw * 8u : kOutOfRange);
-        }
-    };
-    auto stage = [&](int buf, auto set_tag) {
-        constexpr int set = decltype(set_tag)::value;
-#pragma unroll
-        for (int i = 0; i < LW; ++i) Ws[buf][ld_j][ld_r + i * ROWS_PER_PASS] = wregs[set][i];
-#pragma unroll
-        for (int i = 0; i < LA; ++i) As[buf][ld_j][ld_r + i * ROWS_PER_PASS] = aregs[set][i];
-    };
-    constexpr std::integral_constant<int, 0> set0{};
-    constexpr std::integral_constant<int, NSETS - 1> set1{};
-
-    Acc<OP> acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int c = 0; c < TN; ++c) acc[i][c].clear();
-
     // Lane-owned rows/columns inside the wavefront tile: pairs at a stride of 16, so
     // that one 128-bit LDS read is contiguous over the eight lane groups.
     const int wrow = wave_m * 8 * TM + ly * 2;
     const int wcol = wave_n * 8 * TN + lx * 2;
 
-    auto read_frag = [&](int buf, int j, plane2 (&w)[TM], plane2 (&a)[TN]) {
-#pragma unroll
-        for (int q = 0; q < TM / 2; ++q) {
-            const uint4 v = *reinterpret_cast<const uint4*>(&Ws[buf][j][wrow + q * 16]);
-            w[2 * q].x = v.x; w[2 * q].y = v.y;
-            w[2 * q + 1].x = v.z; w[2 * q + 1].y = v.w;
-        }
-#pragma unroll
-        for (int q = 0; q < TN / 2; ++q) {
-            const uint4 v = *reinterpret_cast<const uint4*>(&As[buf][j][wcol + q * 16]);
-            a[2 * q].x = v.x; a[2 * q].y = v.y;
-            a[2 * q + 1].x = v.z; a[2 * q + 1].y = v.w;
-        }
+    Acc<OP> acc[TM][TN];
+    int row0 = 0, col0 = 0;
+    // The SIMD's arbiter favours its oldest wavefront: of the workgroups that share a compute unit the
+    // first would run ahead and finish early, and the last would do its final stages alone, when a SIMD
+    // issues at half its rate (measured: four equal workgroups per compute unit finished at 17, 24, 31 and
+    // 38 us).  Every wavefront therefore lowers its own priority as its share of the work proceeds (four
+    // levels), which keeps the workgroups of a compute unit within a quarter of their work of each other.
+    // (Not for the 128 x 128 tile: its workgroups come in several rounds per compute unit, and 4096^3 was
+    // measured 3.6 % slower with it.)
+    constexpr bool kPaced = TM * TN <= 16;
+    int work_done = 0, work_total = 1;
+    auto pace = [&]() {
+        if constexpr (!kPaced) return;
+        const int q = (4 * work_done) / work_total;
+        if (q <= 0) __builtin_amdgcn_s_setprio(3);
+        else if (q == 1) __builtin_amdgcn_s_setprio(2);
+        else if (q == 2) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
+        ++work_done;
     };
 
-    const int nkt = (p.Kw + KT - 1) / KT;
-    // One stage of the K loop from LDS buffer buf.  Fragments of k-word j+1 are read from LDS
-    // while k-word j is consumed.  The scheduling fences keep the compiler from hoisting every
-    // LDS read of the stage to its top (which needs more registers than there are).
-    auto compute = [&](int kt, int buf) {
-        {
-            // jn = k-words of this stage that exist (all KT except in the last, partial stage);
-            // the per-word test is a scalar branch
-            const int jn = p.Kw - kt * KT;
-            plane2 w[2][TM], a[2][TN];
-            read_frag(buf, 0, w[0], a[0]);
+    // Logical tiles are ordered in bands of kBand tile rows walked column by column, so that the
+    // ~64 tiles resident on one XCD at a time form a roughly square block (8 weight panels x 8
+    // activation panels) and share their operand panels in that XCD's L2.
+    auto locate_tile = [&](int t) {
+        constexpr int kBand = 8;
+        const int band = t / (kBand * tiles_n);
+        const int band_m0 = band * kBand;
+        const int band_rows = (tiles_m - band_m0) < kBand ? (tiles_m - band_m0) : kBand;
+        const int in_band = t - band * kBand * tiles_n;
+        row0 = (band_m0 + in_band % band_rows) * BM;
+        col0 = (in_band / band_rows) * BN;
+    };
+
+    // Accumulates the K stages [kt0, kt1) of the tile at (row0, col0) into acc (cleared first).
+    auto run_stages = [&](const int kt0, const int kt1) {
+        // ---- global addressing of the staged loads ------------------------------------------
+        // Both operands are read through buffer resources: a load whose byte offset is at or
+        // beyond num_records returns zero, which takes care of rows past M / N without any
+        // branch; k-words past the end of a row are sent to kOutOfRange on purpose.
+        constexpr uint32_t kOutOfRange = 0x80000000u;
+        constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format
+        const int64_t wbase = (int64_t)row0 * p.Kw;
+        const int64_t wleft = ((int64_t)p.M * p.Kw - wbase) * (int64_t)sizeof(plane2);
+        const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<plane2*>(p.W + wbase), 0, (int)(wleft < 0x7FFFFFFFLL ? wleft : 0x7FFFFFFFLL), kRsrcFlags);
+        uint32_t woff[LW];
 #pragma unroll
-            for (int j = 0; j < KT; ++j) {
-                if (j >= jn) break;
-                if (j + 1 < KT && j + 1 < jn) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
-                FATNN_VOP3_RUN_PHASE();
+        for (int i = 0; i < LW; ++i) woff[i] = (uint32_t)(ld_r + i * ROWS_PER_PASS) * (uint32_t)p.Kw * 8u;
+
+        int64_t abase, aleft;
+        uint32_t aoff[LA];   // GEMM: byte offset of the row.  conv: byte offset of the column's image
+        int hi0[LA], wi0[LA];
+        if (CONV) {
+            const int64_t img = (int64_t)p.H * p.Wd * p.Cw;          // word pairs per image
+            const int b0 = col0 / (p.Ho * p.Wo);
+            abase = (int64_t)b0 * img;
+            aleft = ((int64_t)p.B * img - abase) * (int64_t)sizeof(plane2);
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < LA; ++i) {
+                const int n = col0 + ld_r + i * ROWS_PER_PASS;
+                const int nn = n < p.N ? n : col0;   // columns past N are never stored; keep them in range
+                const int wo = nn % p.Wo;
+                const int t = nn / p.Wo;
+                const int ho = t % p.Ho;
+                const int b = t / p.Ho;
+                hi0[i] = ho * p.stride - p.pad;
+                wi0[i] = wo * p.stride - p.pad;
+                aoff[i] = (uint32_t)(b - b0) * (uint32_t)img * 8u;
+            }
+        } else {
+            abase = (int64_t)col0 * p.Kw;
+            aleft = ((int64_t)p.N * p.Kw - abase) * (int64_t)sizeof(plane2);
 #pragma unroll
-                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
-                __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < LA; ++i) {
+                hi0[i] = wi0[i] = 0;
+                aoff[i] = (uint32_t)(ld_r + i * ROWS_PER_PASS) * (uint32_t)p.Kw * 8u;
+            }
+        }
+        const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<plane2*>(p.A + abase), 0, (int)(aleft < 0x7FFFFFFFLL ? aleft : 0x7FFFFFFFLL), kRsrcFlags);
+
+        auto load2 = [](const __amdgpu_buffer_rsrc_t& r, uint32_t off) {
+            const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+            plane2 o;
+            o.x = v[0];
+            o.y = v[1];
+            return o;
+        };
+
+        // Small tiles finish a stage faster than a global load returns, so they keep two stages in
+        // flight (two register sets); the large tiles have no registers to spare for that.
+        constexpr bool kTwoAhead = (LW + LA) <= 4;
+        constexpr int NSETS = kTwoAhead ? 2 : 1;
+        plane2 wregs[NSETS][LW], aregs[NSETS][LA];
+        auto fetch = [&](int kt, auto set_tag) {
+            constexpr int set = decltype(set_tag)::value;
+            plane2(&wreg)[LW] = wregs[set];
+            plane2(&areg)[LA] = aregs[set];
+            const int kw = kt * KT + ld_j;
+            const bool kok = kw < p.Kw;
+#pragma unroll
+            for (int i = 0; i < LW; ++i) wreg[i] = load2(wrsrc, kok ? woff[i] + (uint32_t)kw * 8u : kOutOfRange);
+            if (CONV) {
+                // k-word -> (filter tap, channel word); c is innermost in K
+                const int kwc = kok ? kw : 0;
+                const int tap = kwc / p.Cw;
+                const int cw = kwc - tap * p.Cw;
+                const int r = tap / p.S;
+                const int s = tap - r * p.S;
+#pragma unroll
+                for (int i = 0; i < LA; ++i) {
+                    const int hi = hi0[i] + r;
+                    const int wi = wi0[i] + s;
+                    const bool inside = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd;
+                    const uint32_t off = aoff[i] + (uint32_t)((hi * p.Wd + wi) * p.Cw + cw) * 8u;
+                    plane2 v = load2(arsrc, (kok && inside) ? off : kOutOfRange);
+                    // a padded tap is the value 0; only its low plane can be non-zero (codec 01)
+                    v.y |= (kok && !inside) ? p.pad_y : 0u;
+                    areg[i] = v;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < LA; ++i) areg[i] = load2(arsrc, kok ? aoff[i] + (uint32_t)kw * 8u : kOutOfRange);
+            }
+        };
+        auto stage = [&](int buf, auto set_tag) {
+            constexpr int set = decltype(set_tag)::value;
+#pragma unroll
+            for (int i = 0; i < LW; ++i) Ws[buf][ld_j][ld_r + i * ROWS_PER_PASS] = wregs[set][i];
+#pragma unroll
+            for (int i = 0; i < LA; ++i) As[buf][ld_j][ld_r + i * ROWS_PER_PASS] = aregs[set][i];
+        };
+        constexpr std::integral_constant<int, 0> set0{};
+        constexpr std::integral_constant<int, NSETS - 1> set1{};
+
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int c = 0; c < TN; ++c) acc[i][c].clear();
+
+        auto read_frag = [&](int buf, int j, plane2 (&w)[TM], plane2 (&a)[TN]) {
+#pragma unroll
+            for (int q = 0; q < TM / 2; ++q) {
+                const uint4 v = *reinterpret_cast<const uint4*>(&Ws[buf][j][wrow + q * 16]);
+                w[2 * q].x = v.x; w[2 * q].y = v.y;
+                w[2 * q + 1].x = v.z; w[2 * q + 1].y = v.w;
+            }
+#pragma unroll
+            for (int q = 0; q < TN / 2; ++q) {
+                const uint4 v = *reinterpret_cast<const uint4*>(&As[buf][j][wcol + q * 16]);
+                a[2 * q].x = v.x; a[2 * q].y = v.y;
+                a[2 * q + 1].x = v.z; a[2 * q + 1].y = v.w;
+            }
+        };
+
+        // One stage of the K loop from LDS buffer buf.  Fragments of k-word j+1 are read from LDS
+        // while k-word j is consumed.  The scheduling fences keep the compiler from hoisting every
+        // LDS read of the stage to its top (which needs more registers than there are).
+        auto compute = [&](int kt, int buf) {
+            {
+                // jn = k-words of this stage that exist (all KT except in the last, partial stage);
+                // the per-word test is a scalar branch
+                const int jn = p.Kw - kt * KT;
+                plane2 w[2][TM], a[2][TN];
+                read_frag(buf, 0, w[0], a[0]);
+#pragma unroll
+                for (int j = 0; j < KT; ++j) {
+                    if (j >= jn) break;
+                    if (j + 1 < KT && j + 1 < jn) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+                    FATNN_VOP3_RUN_PHASE();
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        if constexpr (!kTwoAhead) {
+            fetch(kt0, set0);
+            stage(0, set0);
+            __syncthreads();
+            for (int kt = kt0; kt < kt1; ++kt) {
+                const int buf = (kt - kt0) & 1;
+                pace();
+                if (kt + 1 < kt1) fetch(kt + 1, set0);
+                compute(kt, buf);
+                if (kt + 1 < kt1) stage(buf ^ 1, set0);
+                __syncthreads();
+            }
+        } else {
+            // stage kt+1 waits in one register set while stage kt+2 is being loaded into the other
+            fetch(kt0, set0);
+            if (kt0 + 1 < kt1) fetch(kt0 + 1, set1);
+            stage(0, set0);
+            __syncthreads();
+            for (int kt = kt0; kt < kt1; kt += 2) {
+                pace();
+                if (kt + 2 < kt1) fetch(kt + 2, set0);
+                compute(kt, 0);
+                if (kt + 1 < kt1) stage(1, set1);
+                __syncthreads();
+                if (kt + 1 >= kt1) break;
+                pace();
+                if (kt + 3 < kt1) fetch(kt + 3, set1);
+                compute(kt + 1, 1);
+                if (kt + 2 < kt1) stage(0, set0);
+                __syncthreads();
             }
         }
     };
-    if constexpr (!kTwoAhead) {
-        fetch(0, set0);
-        stage(0, set0);
-        __syncthreads();
-        for (int kt = 0; kt < nkt; ++kt) {
-            const int buf = kt & 1;
-            if (kt + 1 < nkt) fetch(kt + 1, set0);
-            compute(kt, buf);
-            if (kt + 1 < nkt) stage(buf ^ 1, set0);
-            __syncthreads();
-        }
-    } else {
-        // stage kt+1 waits in one register set while stage kt+2 is being loaded into the other
-        fetch(0, set0);
-        if (nkt > 1) fetch(1, set1);
-        stage(0, set0);
-        __syncthreads();
-        for (int kt = 0; kt < nkt; kt += 2) {
-            if (kt + 2 < nkt) fetch(kt + 2, set0);
-            compute(kt, 0);
-            if (kt + 1 < nkt) stage(1, set1);
-            __syncthreads();
-            if (kt + 1 >= nkt) break;
-            if (kt + 3 < nkt) fetch(kt + 3, set1);
-            compute(kt + 1, 1);
-            if (kt + 2 < nkt) stage(0, set0);
-            __syncthreads();
-        }
-    }
 
     // ---- epilogue: Eq. 3's subtraction, then the optional fp32 scale -----------------------
+    auto epilogue = [&]() {
     // (column n = col0 + wcol + ... is even, so a pair is 8-byte aligned when the row pitch and the base are)
     const bool pair_c = p.ldc_n == 1 && (p.ldc_m & 1) == 0 && (reinterpret_cast<uintptr_t>(p.C) & 7) == 0;
     const bool pair_f = p.ldf_n == 1 && (p.ldf_m & 1) == 0 && (reinterpret_cast<uintptr_t>(p.Cf) & 7) == 0;
@@ -395,6 +449,90 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
             }
         }
     }
+    };
+
+    const int nkt = (p.Kw + KT - 1) / KT;
+    if constexpr (!STREAMK) {
+        work_total = nkt;
+        locate_tile(logical);
+        run_stages(0, nkt);
+        epilogue();
+    } else {
+        constexpr int kTileWords = TM * TN * Acc<OP>::kWords * NT;   // accumulator words of a tile
+        const int64_t G = gridDim.x;
+        const int nst = sk.nst;
+        auto first_unit = [&](int64_t g) { return (int32_t)((g * (int64_t)sk.units) / G); };
+        const int u_begin = first_unit(logical), u_end = first_unit(logical + 1);
+        if (u_begin >= u_end) return;
+        work_total = u_end - u_begin;
+        const int tile_first = u_begin / nst, tile_last = (u_end - 1) / nst;
+        const int nseg = tile_last - tile_first + 1;
+        // The piece at the end of the range (the tile is finished by the next workgroup) is done first:
+        // both halves of a shared tile are then ready early in the life of their workgroups, and the
+        // hand-over is hidden behind the whole tiles that follow instead of sitting at the kernel's end.
+        const bool tail_piece = u_end < (tile_last + 1) * nst;
+        for (int idx = 0; idx < nseg; ++idx) {
+            const int j = (tail_piece && nseg > 1) ? (idx == 0 ? nseg - 1 : idx - 1) : idx;
+            const int tile = tile_first + j;
+            const int t_begin = tile * nst;
+            const int s0 = (u_begin > t_begin ? u_begin : t_begin) - t_begin;
+            const int s1 = (u_end < t_begin + nst ? u_end : t_begin + nst) - t_begin;
+            locate_tile(tile);
+            run_stages(s0, s1);
+            if (s0 == 0 && s1 == nst) {
+                epilogue();
+                continue;
+            }
+            // A piece of a shared tile.  Its partial popcount sums go to this workgroup's slot (slot 0 = a
+            // piece that continues a tile, slot 1 = a piece that begins one) as device-scope atomic stores,
+            // which write through to the level all XCDs share; the wait below returns when every one of them
+            // has been acknowledged, and only then, after the workgroup's barrier, are the piece's stages
+            // added to the tile's count.  The piece that completes the count reads the other slots with
+            // device-scope atomic loads (which never take a stale line from the XCD's own L2), adds them to
+            // the sums it still holds in registers, and runs the epilogue.  No cache is written back or
+            // invalidated: a release / acquire fence pair around plain stores flushes or drops the XCD's
+            // whole L2, operands included, and was measured four times slower than the plain kernel; adding
+            // all pieces into one slot with atomic read-modify-writes suffered from their contention.
+            int32_t* const mine = sk.partial + ((int64_t)logical * 2 + (s0 == 0 ? 1 : 0)) * kTileWords + tid;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int c = 0; c < TN; ++c)
+#pragma unroll
+                    for (int q = 0; q < Acc<OP>::kWords; ++q)
+                        __hip_atomic_store(mine + ((i * TN + c) * Acc<OP>::kWords + q) * NT, acc[i][c].word(q),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the stores above have completed
+            __syncthreads();
+            if (tid == 0)
+                ticket = __hip_atomic_fetch_add(sk.counters + tile, s1 - s0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const bool last = ticket + (s1 - s0) == nst;
+            __syncthreads();   // everybody has read the ticket before a later piece overwrites it
+            if (!last) continue;
+            // leave the counter at zero for the next launch
+            if (tid == 0) __hip_atomic_store(sk.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // the other pieces of this tile: every workgroup whose range meets [t_begin, t_begin + nst)
+            int64_t g = ((int64_t)t_begin * G) / sk.units;
+            while (g > 0 && first_unit(g) > t_begin) --g;
+            while (first_unit(g + 1) <= t_begin) ++g;
+            for (; g < G && first_unit(g) < t_begin + nst; ++g) {
+                if (g == logical) continue;
+                if (first_unit(g + 1) <= first_unit(g)) continue;   // a workgroup without units
+                const int slot = first_unit(g) > t_begin ? 0 : 1;
+                const int32_t* const theirs = sk.partial + (g * 2 + slot) * kTileWords + tid;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int c = 0; c < TN; ++c)
+#pragma unroll
+                        for (int q = 0; q < Acc<OP>::kWords; ++q)
+                            acc[i][c].word(q) += __hip_atomic_load(theirs + ((i * TN + c) * Acc<OP>::kWords + q) * NT,
+                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            epilogue();
+        }
+    }
 }
 
 template <int OP, int WM, int WN, int TM, int TN>
@@ -407,12 +545,73 @@ int launch_shape(const GemmParams& p, hipStream_t stream) {
     if (ntiles > 0x7FFFFFF0LL) return -2;
     const unsigned grid = (unsigned)(((ntiles + 7) / 8) * 8);
     const LaunchTiming t = take_launch_timing();
+    const StreamKArgs none{};
     if (p.is_conv)
-        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true>), dim3(grid), dim3(64 * WM * WN), 0,
-                              stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, true, false>), dim3(grid), dim3(64 * WM * WN), 0,
+                              stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles, none);
     else
-        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false>), dim3(grid), dim3(64 * WM * WN), 0,
-                              stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles);
+        hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false, false>), dim3(grid), dim3(64 * WM * WN),
+                              0, stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles, none);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Compute units of the current device (asked once per device index; concurrent first calls store the same value).
+int compute_units() {
+    static std::atomic<int> cache[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    const bool cached = dev >= 0 && dev < 16;
+    int v = cached ? cache[dev].load(std::memory_order_relaxed) : 0;
+    if (v == 0) {
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
+        if (cached) cache[dev].store(v, std::memory_order_relaxed);
+    }
+    return v;
+}
+
+// The even-share launch of the 64 x 64 tile (32 x 32 per wavefront, 4 x 4 accumulators per lane for the
+// one-word operators).  Returns 1 when the problem or the workspace does not suit it (the caller then
+// takes a tile-per-workgroup launch), 0 on success, negative on a launch error.
+template <int OP, int TM, int TN>
+int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_per_cu = 0) {
+    constexpr int WM = 2, WN = 2, NT = 256;
+    constexpr int BM = WM * 8 * TM, BN = WN * 8 * TN;
+    constexpr int64_t kTileBytes = (int64_t)TM * TN * Acc<OP>::kWords * NT * 4;
+    if (p.ws == nullptr || p.ws_bytes <= (size_t)kEvenShareCounterBytes) return 1;
+    const int tiles_m = (p.M + BM - 1) / BM;
+    const int64_t tiles_n = ((int64_t)p.N + BN - 1) / BN;
+    const int64_t ntiles = (int64_t)tiles_m * tiles_n;
+    const int nst = (p.Kw + KT - 1) / KT;
+    const int64_t units = ntiles * nst;
+    if (ntiles > kEvenShareCounterBytes / 4 || units >= 0x7FFFFFFFLL) return 1;
+    const int forced = always_per_cu > 0 ? always_per_cu : tuning().gemm_even_share;
+    if (forced == 9) return 1;
+    const int cus = compute_units();
+    const int64_t fit = ((int64_t)p.ws_bytes - kEvenShareCounterBytes) / (2 * kTileBytes);
+    int64_t G;
+    if (forced >= 1 && forced <= 8) {
+        G = (int64_t)cus * forced;
+    } else {
+        // Measured (512 x 3136 x 4609: 38.4 -> 34.9 us, 1536^2 x 4096: 46.9 -> 41.0 us, 2048^3 equal,
+        // 3072^3 and 256 x 12544 x 1152 slower): the even shares pay where the tiles would not give every
+        // compute unit four workgroups and K is long enough (a dozen stages) to carry the hand-over.
+        if (ntiles >= 4 * (int64_t)cus || nst < 12) return 1;
+        // four workgroups (= four wavefronts per SIMD) per compute unit, but at least four stages each
+        G = (int64_t)cus * 4;
+        if (G > units / 4) G = units / 4;
+    }
+    if (G > units) G = units;
+    G = (G + 7) & ~(int64_t)7;   // the XCD mapping wants a multiple of 8; workgroups without units return at once
+    if (G > fit) G = fit & ~(int64_t)7;
+    if (G < 8) return 1;
+    StreamKArgs sk{};
+    sk.counters = reinterpret_cast<int32_t*>(p.ws);
+    sk.partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.ws) + kEvenShareCounterBytes);
+    sk.nst = nst;
+    sk.units = (int32_t)units;
+    const LaunchTiming t = take_launch_timing();
+    hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false, true>), dim3((unsigned)G), dim3(NT), 0, stream,
+                          t.start, t.stop, 0, p, tiles_m, (int)ntiles, sk);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -420,19 +619,29 @@ int launch_shape(const GemmParams& p, hipStream_t stream) {
 // accumulators per lane, six wavefronts per SIMD) matches the 128 x 128 tile (8 x 8 accumulators, three per
 // SIMD) up to 8192^3 and beats it below about 16 K wavefront tiles of 64 x 64, where tile quantisation
 // over 256 CUs matters; the large tile keeps a few per cent on very large problems with a shallow K
-// (fewer operand re-reads).  Below about a thousand such tiles the 32 x 32 tile (2 x 2 accumulators) puts
-// four times as many wavefronts to work and wins by up to 30 % (4096 x 64 x 4608: 25 -> 18 us,
-// 1536^2 x 4096: 53 -> 41 us); at 2048^2 the two are equal, at 3072^3 the 64 x 64 tile is 6 % faster.
+// (fewer operand re-reads).  Below that size, and given a workspace, the 64 x 64 tile runs under the
+// even-share schedule, which has no tile quantisation at all.  Without a workspace: below about a thousand
+// 64 x 64 wavefront tiles the 32 x 32 tile (2 x 2 accumulators) puts four times as many wavefronts to work
+// (4096 x 64 x 4608: 25 -> 18 us, 1536^2 x 4096: 53 -> 41 us) but reads LDS once per 8 instruction pairs.
 template <int OP, int TM, int TN>
 int launch_op(const GemmParams& p, hipStream_t stream) {
     constexpr int WTM = 8 * TM, WTN = 8 * TN;
     const int64_t wave_tiles = (((int64_t)p.M + WTM - 1) / WTM) * (((int64_t)p.N + WTN - 1) / WTN);
     if (wave_tiles >= 16 * 1024 && p.M > WTM) return launch_shape<OP, 2, 2, TM, TN>(p, stream);
+    if (!p.is_conv) {
+        const int rc = launch_even_share<OP, TM / 2, TN / 2>(p, stream);
+        if (rc <= 0) return rc;
+    }
     if (wave_tiles >= 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
     return launch_shape<OP, 2, 2, 2, 2>(p, stream);
 }
 
 }  // namespace
+
+int launch_ternary_gemm_even_share(const GemmParams& p, int wgs_per_cu, hipStream_t stream) {
+    if (p.M == 0 || p.N == 0) return 0;
+    return launch_even_share<OP_TERNARY, 4, 4>(p, stream, wgs_per_cu);
+}
 
 int launch_gemm(const GemmParams& p, int op, hipStream_t stream) {
     if (p.M == 0 || p.N == 0) return 0;

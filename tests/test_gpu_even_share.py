@@ -1,0 +1,99 @@
+"""The even-share ("stream-K") schedule of the tiled GEMM against the CPU oracle, bit-exact: every
+workgroups-per-compute-unit setting, shapes whose tiles are cut between two workgroups and shapes whose
+tiles are shared by many, ragged M / N / K, all operators, the fp32 epilogue, small workspaces, and
+repeated calls on one workspace (the tile counters must come back to zero)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from test_gpu_parity import dev, DEV
+
+pytestmark = pytest.mark.gpu
+
+fatnn = pytest.importorskip("paper_2008_05101_amd")
+
+CODE = np.array([0, 1, 3], dtype=np.int8)
+
+
+def counters_are_zero(ws):
+    return not bool(ws[:65536].view(torch.int32).any().item())
+
+
+@pytest.mark.parametrize("per_cu", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("M,N,K", [(512, 3136, 4609), (4096, 32, 4608), (200, 130, 2500), (70, 1000, 777)])
+def test_even_share_every_split_count(tuning, per_cu, M, N, K):
+    tuning(gemm_even_share=per_cu)
+    rnd = np.random.default_rng(M + N + K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    ws = fatnn.gemm_workspace(DEV)
+    want = oracle.ternary_gemm(Lw, La, 0)
+    for _ in range(2):                       # the second call finds the counters as the first left them
+        C, _ = fatnn.ternary_gemm(Wp, Ap, M, N, K, 0, workspace=ws)
+        assert np.array_equal(C.cpu().numpy(), want)
+        assert counters_are_zero(ws)
+
+
+@pytest.mark.parametrize("M,N,K,mode", [(4096, 17, 4608, 0), (4096, 64, 4608, 1), (4096, 128, 4608, 0),
+                                        (1000, 100, 9216, 1), (1536, 1536, 4096, 0), (64, 64, 65536, 0),
+                                        (65, 65, 8192, 1), (333, 77, 3000, 0)])
+def test_even_share_automatic_choice_matches_oracle(M, N, K, mode):
+    rnd = np.random.default_rng(M * 3 + N + K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    scale = rnd.uniform(0.5, 1.5, M).astype(np.float32)
+    bias = rnd.standard_normal(M).astype(np.float32)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    C, Cf = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, scale=dev(scale), bias=dev(bias))
+    want = oracle.ternary_gemm(Lw, La, mode)
+    assert np.array_equal(C.cpu().numpy(), want)
+    assert np.array_equal(Cf.cpu().numpy(), oracle.scale_epilogue(want, scale, bias, channel_is_row=True))
+    # and the plain call (no workspace) gives the same
+    C0, _ = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, workspace=None)
+    assert torch.equal(C, C0)
+
+
+@pytest.mark.parametrize("nbytes", [65536, 65536 + 8 * 2 * 16384, 65536 + 100 * 2 * 16384, 1 << 20])
+def test_even_share_small_workspaces(tuning, nbytes):
+    tuning(gemm_even_share=4)
+    case = si.cfg5_ragged()
+    Lw, La = case.make()
+    Lw, La = Lw[:256], La[:700]
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    ws = fatnn.gemm_workspace(DEV, nbytes)
+    C, _ = fatnn.ternary_gemm(Wp, Ap, 256, 700, case.K, 0, workspace=ws)
+    assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
+    assert counters_are_zero(ws)
+
+
+@pytest.mark.parametrize("basis", [0, 1, 2])
+def test_even_share_twobit_and_binary_operators(tuning, basis):
+    tuning(gemm_even_share=3)
+    rnd = np.random.default_rng(70 + basis)
+    M, N, K = 300, 200, 3000
+    if basis == 2:                                   # the xnor-only ablation runs on ternary codecs
+        Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+        La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+        from oracle import alg1
+        want = alg1.gemm_xnor_only(Lw[:8], La[:6])
+        C = fatnn.twobit_gemm(fatnn.pack_twobit(dev(CODE[Lw])), fatnn.pack_twobit(dev(CODE[La])), M, N, K, basis)
+        assert np.array_equal(C.cpu().numpy()[:8, :6], want)
+        C0 = fatnn.twobit_gemm(fatnn.pack_twobit(dev(CODE[Lw])), fatnn.pack_twobit(dev(CODE[La])), M, N, K, basis,
+                               workspace=None)
+        assert torch.equal(C, C0)
+    else:
+        Qw = rnd.integers(0, 4, size=(M, K), dtype=np.int8)
+        Qa = rnd.integers(0, 4, size=(N, K), dtype=np.int8)
+        C = fatnn.twobit_gemm(fatnn.pack_twobit(dev(Qw)), fatnn.pack_twobit(dev(Qa)), M, N, K, basis)
+        assert np.array_equal(C.cpu().numpy(), oracle.twobit_gemm(Qw, Qa, basis))
+    Bw = rnd.integers(0, 2, size=(M, K + 37), dtype=np.int8)
+    Ba = rnd.integers(0, 2, size=(N, K + 37), dtype=np.int8)
+    Cb = fatnn.binary_gemm(fatnn.pack_binary(dev(Bw)), fatnn.pack_binary(dev(Ba)), M, N, K + 37)
+    assert np.array_equal(Cb.cpu().numpy(), oracle.binary_gemm(Bw, Ba))
+    assert counters_are_zero(fatnn.gemm_workspace(DEV))

@@ -28,7 +28,7 @@ def kernels():
         subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
         text = open(out).read()
     bodies = {}
-    for m in re.finditer(r"^(_ZN5fatnn\w*plane_gemm_kernelILi(\d)ELi2ELi2ELi8ELi8ELb0EE\w*):[^\n]*\n(.*?)s_endpgm", text,
+    for m in re.finditer(r"^(_ZN5fatnn\w*plane_gemm_kernelILi(\d)ELi2ELi2ELi8ELi8ELb0ELb0EE\w*):[^\n]*\n(.*?)s_endpgm", text,
                          re.S | re.M):
         bodies[int(m.group(2))] = m.group(3)
     return bodies
