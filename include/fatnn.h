@@ -282,6 +282,23 @@ int fatnn_twobit_gemm_ws(const void *Wp, const void *Ap, int64_t M, int64_t N, i
 int fatnn_binary_gemm_ws(const void *Wb, const void *Ab, int64_t M, int64_t N, int64_t K, int32_t *C,
                          int64_t ldc, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * fatnn_ternary_gemm_ws for callers that cannot allocate device memory and have no workspace to hand in:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * bit-identical results; it always runs the equal-shares schedule, and the scratch memory of that schedule
+ * (tile counters and hand-over slots) is a fixed array inside the library, fatnn_noalloc_scratch_bytes()
+ * = 64 KiB + 16 MiB on every GPU the library has run this call on, held until the process ends.  The call
+ * allocates and frees nothing.
+ *   limits   ceil(M/64) * ceil(N/64) <= 16384 tiles (one counter each); beyond that FATNN_ERR_SIZE.
+ *   state    every call on one GPU uses that GPU's one array: calls that overlap on a GPU (two streams,
+ *            two threads) race and give wrong results; order them.  The call clears what it needs of the
+ *            array itself (with a fill kernel, so it may be captured into a HIP graph).
+ */
+size_t fatnn_noalloc_scratch_bytes(void);
+int fatnn_ternary_gemm_noalloc(const void *Wp, const void *Ap, int64_t M, int64_t N, int64_t K, int act_mode,
+                               int32_t *C, int64_t ldc, const float *scale, const float *bias, float *Cf,
+                               int64_t ldcf, void *stream);
+
 /* FATNN_OK for a zero count of out-of-set inputs, FATNN_ERR_LEVEL otherwise (first constraint of
  * Section 3.3).  `n_invalid_host` is the value of a packing call's counter copied to the host. */
 int fatnn_level_status(int64_t n_invalid_host);

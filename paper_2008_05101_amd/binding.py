@@ -26,7 +26,7 @@ EXPORTS = [
     "fatnn_ternary_gemm", "fatnn_ternary_conv2d", "fatnn_pack_twobit", "fatnn_twobit_gemm",
     "fatnn_twobit_conv2d", "fatnn_binary_packed_bytes", "fatnn_pack_binary", "fatnn_binary_gemm",
     "fatnn_gemm_workspace_bytes", "fatnn_gemm_workspace_init", "fatnn_ternary_gemm_ws", "fatnn_twobit_gemm_ws",
-    "fatnn_binary_gemm_ws",
+    "fatnn_binary_gemm_ws", "fatnn_noalloc_scratch_bytes", "fatnn_ternary_gemm_noalloc",
     "fatnn_time_next_launch", "fatnn_set_tuning", "fatnn_level_status",
     "fatnn_probe_scratch_bytes", "fatnn_probe_valu", "fatnn_probe_hbm", "fatnn_status_str", "fatnn_version",
 ]
@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
         l.fatnn_gemm_workspace_bytes.restype = sz
         l.fatnn_gemm_workspace_init.argtypes = [vp, sz, vp]
         l.fatnn_ternary_gemm_ws.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, i64, vp, sz, vp]
+        l.fatnn_noalloc_scratch_bytes.restype = sz
+        l.fatnn_ternary_gemm_noalloc.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, i64, vp]
         l.fatnn_twobit_gemm_ws.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, sz, vp]
         l.fatnn_binary_gemm_ws.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, sz, vp]
         l.fatnn_level_status.argtypes = [i64]
@@ -404,6 +406,17 @@ def ternary_gemm(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, act
                                        _ptr(bias), _ptr(out_f), max(ldcf, N), _ptr(ws),
                                        0 if ws is None else ws.numel(), _stream()), "fatnn_ternary_gemm_ws")
     return out, out_f
+
+
+def ternary_gemm_noalloc(Wp: torch.Tensor, Ap: torch.Tensor, M: int, N: int, K: int, act_mode: int,
+                         out: Optional[torch.Tensor], scale: Optional[torch.Tensor] = None,
+                         bias: Optional[torch.Tensor] = None, out_f: Optional[torch.Tensor] = None) -> None:
+    """fatnn_ternary_gemm_noalloc: the caller brings every output; nothing is allocated here or in the library."""
+    ldc = out.stride(0) if out is not None and out.dim() == 2 and M > 0 else N
+    ldcf = out_f.stride(0) if out_f is not None and out_f.dim() == 2 and M > 0 else N
+    _check(lib().fatnn_ternary_gemm_noalloc(_ptr(Wp), _ptr(Ap), M, N, K, act_mode, _ptr(out), max(ldc, N), _ptr(scale),
+                                            _ptr(bias), _ptr(out_f), max(ldcf, N), _stream()),
+           "fatnn_ternary_gemm_noalloc")
 
 
 def _conv_out_hw(H: int, W: int, R: int, S: int, stride: int, pad: int) -> Tuple[int, int]:

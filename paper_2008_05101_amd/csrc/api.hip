@@ -599,6 +599,80 @@ int fatnn_ternary_conv2d_chain(const void* Wp, const void* Xp, int x_layout, int
                     bias, Yf, stream, &ch);
 }
 
+// ---- the entry point that allocates nothing -------------------------------------------------------------
+// Scratch of the even-share schedule in a file-scope device array: tile counters followed by two hand-over
+// slots (64 x 64 int32 each) for 512 workgroups.  Every GPU the library runs on holds its own copy until
+// the process ends.  The array's name is a host-side stand-in; the device address is asked for once per
+// device (with that device current) and only that address is ever handed to a launch.
+namespace {
+constexpr int kNoAllocWorkgroups = 512;
+constexpr size_t kNoAllocScratchBytes = (size_t)kEvenShareCounterBytes + (size_t)kNoAllocWorkgroups * 2 * (64 * 64 * 4);
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int scratch_for_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FATNN_ERR_HIP;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return FATNN_ERR_HIP;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // concurrent first calls store the same address
+    }
+    *out = ptr;
+    return FATNN_OK;
+}
+}  // namespace
+
+size_t fatnn_noalloc_scratch_bytes(void) { return kNoAllocScratchBytes; }
+
+int fatnn_ternary_gemm_noalloc(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int act_mode,
+                               int32_t* C, int64_t ldc, const float* scale, const float* bias, float* Cf,
+                               int64_t ldcf, void* stream) {
+    int rc = check_gemm_dims(M, N, K);
+    if (rc != FATNN_OK) return rc;
+    if (act_mode != FATNN_SYM && act_mode != FATNN_RELU) return FATNN_ERR_UNSUPPORTED;
+    // the scratch has one counter per 64 x 64 tile
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    const int64_t stages = (fatnn_words_per_row(K) + 7) / 8;
+    if (tiles > kEvenShareCounterBytes / 4 || tiles * stages >= 0x7FFFFFFFLL) return FATNN_ERR_SIZE;
+    if (M == 0 || N == 0) return FATNN_OK;
+    if (C == nullptr && Cf == nullptr) return FATNN_ERR_NULL;
+    if (Cf != nullptr && scale == nullptr) return FATNN_ERR_NULL;
+    if (C != nullptr && ldc < N) return FATNN_ERR_SHAPE;
+    if (Cf != nullptr && ldcf < N) return FATNN_ERR_SHAPE;
+    if (Wp == nullptr || Ap == nullptr) return FATNN_ERR_NULL;
+    if (!aligned(Wp, 16) || !aligned(Ap, 16) || !aligned(C, 4) || !aligned(Cf, 4) || !aligned(scale, 4) ||
+        !aligned(bias, 4))
+        return FATNN_ERR_ALIGN;
+    void* ptr = nullptr;
+    rc = scratch_for_current_device(&ptr);
+    if (rc != FATNN_OK) return rc;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // The array keeps what the last call left.  A completed call leaves the counters at zero, but a call
+    // must not depend on that: the counters of this call's tiles are cleared first, with a fill kernel
+    // (which, unlike a memset node, is safe inside a captured graph).
+    plane2 zero;
+    zero.x = 0u;
+    zero.y = 0u;
+    if (launch_fill_words(reinterpret_cast<plane2*>(ptr), (tiles * 4 + 7) / 8, zero, st) != 0) return FATNN_ERR_HIP;
+    GemmParams p{};
+    p.ws = ptr;
+    p.ws_bytes = kNoAllocScratchBytes;
+    p.W = reinterpret_cast<const plane2*>(Wp);
+    p.A = reinterpret_cast<const plane2*>(Ap);
+    set_ternary_consts(p, Wp, M, K, act_mode);
+    p.K = (int32_t)K;
+    p.M = (int32_t)M;
+    p.N = (int32_t)N;
+    p.Kw = (int32_t)fatnn_words_per_row(K);
+    p.C = C; p.ldc_m = ldc; p.ldc_n = 1;
+    p.Cf = Cf; p.ldf_m = ldcf; p.ldf_n = 1;
+    p.scale = scale; p.bias = bias;
+    p.is_conv = 0;
+    return launch_ternary_gemm_even_share(p, 2, st) == 0 ? FATNN_OK : FATNN_ERR_HIP;
+}
+
 int fatnn_twobit_gemm(const void* Wp, const void* Ap, int64_t M, int64_t N, int64_t K, int basis, int32_t* C,
                       int64_t ldc, void* stream) {
     return fatnn_twobit_gemm_ws(Wp, Ap, M, N, K, basis, C, ldc, nullptr, 0, stream);
