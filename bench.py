@@ -96,9 +96,10 @@ def time_kernel_ms(torch, fn, iters, warmup):
     return e0.elapsed_time(e1) / iters
 
 
-def time_graph_ms(torch, fn, iters, replays=5):
+def time_graph_ms(torch, fn, iters, replays=5, min_ms=40.0):
     """Average duration of fn's launches with the host out of the picture: `iters` calls recorded into one
-    HIP graph (library kernels only), replayed `replays` times."""
+    HIP graph (library kernels only), replayed at least `replays` times and for at least `min_ms` (a
+    measurement of a few milliseconds is over before the clocks have settled and reads up to 8 % slow)."""
     fn()
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -106,16 +107,20 @@ def time_graph_ms(torch, fn, iters, replays=5):
         for _ in range(iters):
             fn()
     torch.cuda.synchronize()
-    graph.replay()
-    torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(replays):
-        graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / (iters * replays)
+
+    def run(n):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+    first = run(1)
+    n = max(replays, int(min_ms / max(first, 1e-3)) + 1)
+    run(max(1, n // 2))            # untimed: brings the clocks up
+    return run(n) / (iters * n)
 
 
 class HipEvents:
@@ -340,6 +345,14 @@ def other_config_summaries(torch, fatnn, si, dev, peaks):
     C = torch.empty((g.M, g.N), dtype=torch.int32, device=dev)
     t = time_graph_ms(torch, lambda: fatnn.ternary_gemm(Wp, Ap, g.M, g.N, g.K, g.act_mode, out=C), 20)
     out[f"cfg5a_gemm_{g.M}x{g.N}x{g.K}"] = tops(g.macs(), t)
+    # fully connected layers (Supplementary S1: convolutions whose filter covers the map) at batch 16-128
+    Wfc = torch.randint(0, 3, (4096, 4608), dtype=torch.int8, device=dev)
+    Wp = fatnn.pack_ternary(Wfc, fatnn.WEIGHT)
+    for n in (16, 32, 64, 128):
+        Ap = fatnn.pack_ternary(torch.randint(0, 3, (n, 4608), dtype=torch.int8, device=dev), fatnn.ACT)
+        C = torch.empty((4096, n), dtype=torch.int32, device=dev)
+        t = time_graph_ms(torch, lambda: fatnn.ternary_gemm(Wp, Ap, 4096, n, 4608, 0, out=C), 20)
+        out[f"fc_4096x{n}x4608"] = tops(4096 * n * 4608, t)
     return out
 
 

@@ -82,7 +82,7 @@ def lib() -> ctypes.CDLL:
         l.fatnn_pack_binary.argtypes = [vp, i64, i64, vp, sz, vp, vp]
         l.fatnn_binary_gemm.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
         l.fatnn_time_next_launch.argtypes = [vp, vp]
-        l.fatnn_set_tuning.argtypes = [i32, i32, i32, i32]
+        l.fatnn_set_tuning.argtypes = [i32, i32, i32, i32, i32]
         l.fatnn_gemm_workspace_bytes.restype = sz
         l.fatnn_gemm_workspace_init.argtypes = [vp, sz, vp]
         l.fatnn_ternary_gemm_ws.argtypes = [vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, vp, i64, vp, sz, vp]
@@ -156,9 +156,10 @@ def binary_gemm(Wb: torch.Tensor, Ab: torch.Tensor, M: int, N: int, K: int,
 
 
 def set_tuning(conv_kernel: int = -1, stream_wps: int = -1, seven_pixel_groups: int = -1,
-               gemm_even_share: int = -1) -> None:
+               gemm_even_share: int = -1, gemm_deepk: int = -1) -> None:
     """fatnn_set_tuning: process-wide measurement switches; -1 keeps a value."""
-    _check(lib().fatnn_set_tuning(conv_kernel, stream_wps, seven_pixel_groups, gemm_even_share), "fatnn_set_tuning")
+    _check(lib().fatnn_set_tuning(conv_kernel, stream_wps, seven_pixel_groups, gemm_even_share, gemm_deepk),
+           "fatnn_set_tuning")
 
 
 _workspaces = {}

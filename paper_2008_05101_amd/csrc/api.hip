@@ -19,7 +19,7 @@ thread_local LaunchTiming g_timing = {nullptr, nullptr};
 // thread-safe); fatnn_set_tuning overwrites them; launches only read them.
 namespace {
 struct TuningState {
-    std::atomic<int> force_tiled, stream_wps, u7_mode, gemm_even_share;
+    std::atomic<int> force_tiled, stream_wps, u7_mode, gemm_even_share, gemm_deepk;
     TuningState() {
         const char* e = getenv("FATNN_CONV_KERNEL");
         force_tiled.store(e != nullptr && e[0] == 't' ? 1 : 0);
@@ -30,6 +30,8 @@ struct TuningState {
         u7_mode.store((e != nullptr && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 1);
         e = getenv("FATNN_GEMM_EVEN_SHARE");
         gemm_even_share.store((e != nullptr && e[0] >= '0' && e[0] <= '9') ? e[0] - '0' : 0);
+        e = getenv("FATNN_GEMM_DEEPK");
+        gemm_deepk.store((e != nullptr && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 0);
     }
 };
 TuningState& tuning_state() {
@@ -44,14 +46,16 @@ Tuning tuning() {
     v.stream_wps = s.stream_wps.load(std::memory_order_relaxed);
     v.u7_mode = s.u7_mode.load(std::memory_order_relaxed);
     v.gemm_even_share = s.gemm_even_share.load(std::memory_order_relaxed);
+    v.gemm_deepk = s.gemm_deepk.load(std::memory_order_relaxed);
     return v;
 }
-void set_tuning(int force_tiled, int stream_wps, int u7_mode, int gemm_even_share) {
+void set_tuning(int force_tiled, int stream_wps, int u7_mode, int gemm_even_share, int gemm_deepk) {
     TuningState& s = tuning_state();
     if (force_tiled >= 0) s.force_tiled.store(force_tiled != 0 ? 1 : 0, std::memory_order_relaxed);
     if (stream_wps >= 0) s.stream_wps.store(stream_wps, std::memory_order_relaxed);
     if (u7_mode >= 0) s.u7_mode.store(u7_mode, std::memory_order_relaxed);
     if (gemm_even_share >= 0) s.gemm_even_share.store(gemm_even_share, std::memory_order_relaxed);
+    if (gemm_deepk >= 0) s.gemm_deepk.store(gemm_deepk, std::memory_order_relaxed);
 }
 LaunchTiming take_launch_timing() {
     const LaunchTiming t = g_timing;
@@ -780,9 +784,10 @@ int fatnn_probe_hbm(int kind, void* dst, const void* src, size_t bytes, void* sc
 
 int fatnn_level_status(int64_t n_invalid_host) { return n_invalid_host == 0 ? FATNN_OK : FATNN_ERR_LEVEL; }
 
-int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups, int gemm_even_share) {
-    if (conv_kernel > 1 || stream_wps > 8 || seven_pixel_groups > 2 || gemm_even_share > 9) return FATNN_ERR_UNSUPPORTED;
-    fatnn::set_tuning(conv_kernel, stream_wps, seven_pixel_groups, gemm_even_share);
+int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups, int gemm_even_share, int gemm_deepk) {
+    if (conv_kernel > 1 || stream_wps > 8 || seven_pixel_groups > 2 || gemm_even_share > 9 || gemm_deepk > 2)
+        return FATNN_ERR_UNSUPPORTED;
+    fatnn::set_tuning(conv_kernel, stream_wps, seven_pixel_groups, gemm_even_share, gemm_deepk);
     return FATNN_OK;
 }
 

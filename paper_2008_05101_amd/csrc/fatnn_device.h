@@ -107,10 +107,11 @@ struct Tuning {
     int stream_wps;     // wavefronts per SIMD of the streaming kernel (0 = planned)
     int u7_mode;        // seven-pixel groups: 0 off, 1 by the size rule, 2 wherever a kernel exists
     int gemm_even_share;  // even-share GEMM schedule: 0 automatic, 1..8 workgroups per CU forced, 9 never
+    int gemm_deepk;       // few-column / long-K kernel: 0 automatic, 1 wherever the shape fits, 2 never
 };
 Tuning tuning();
 // a negative value keeps the current one
-void set_tuning(int force_tiled, int stream_wps, int u7_mode, int gemm_even_share);
+void set_tuning(int force_tiled, int stream_wps, int u7_mode, int gemm_even_share, int gemm_deepk);
 
 // Column-streaming convolution (weights resident in registers, activations through
 // the scalar cache).  Input: bordered packed activations [B][Hp][Wp][Cw] (+ slack),

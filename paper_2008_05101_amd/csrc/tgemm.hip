@@ -535,6 +535,250 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
     }
 }
 
+int compute_units();
+
+// ---- few columns, long K: fully connected layers at batch 17-128 -------------------------------------
+// Supplementary S1 treats a fully connected layer as a convolution whose filter covers the whole feature
+// map: a GEMM with few columns (the batch) and a long K.  Its output has too few tiles to fill the chip and
+// each tile's K loop is a chain of load latencies, so here the K range of a BM x 32 output tile is split
+// over the eight wavefronts of a workgroup.  Every wavefront computes the whole tile over its eighth of K
+// (8 x 8 lanes, TM x 4 accumulators per lane) from operands it stages itself in a private part of LDS --
+// no barrier inside the K loop, the wavefronts run freely -- and the eight partial popcount sums of Eq. 3
+// meet in LDS once, at the end, where each thread finishes two neighbouring outputs.
+constexpr int DK_WAVES = 8;       // wavefronts per workgroup = parts of K
+constexpr int DK_KC = 16;         // k-words staged per chunk
+constexpr int DK_BN = 32;         // columns per tile
+
+template <int OP, int TM>
+__global__ __launch_bounds__(64 * DK_WAVES) void deepk_gemm_kernel(const GemmParams p, const int tiles_m) {
+    constexpr int TN = 4, BM = 8 * TM, BN = DK_BN;
+    constexpr int PW = BM + LDS_PAD, PA = BN + LDS_PAD;
+    constexpr int kAccWords = TM * TN * Acc<OP>::kWords;
+    constexpr int kStageBytes = DK_KC * (PW + PA) * (int)sizeof(plane2);   // per wavefront
+    constexpr int kReduceBytes = kAccWords * 64 * 4;                       // per wavefront
+    constexpr int kWaveBytes = kStageBytes > kReduceBytes ? kStageBytes : kReduceBytes;
+    __shared__ __attribute__((aligned(16))) char lds[DK_WAVES * kWaveBytes];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ly = lane >> 3, lx = lane & 7;
+    const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+
+    plane2(*Ws)[PW] = reinterpret_cast<plane2(*)[PW]>(lds + wave * kWaveBytes);
+    plane2(*As)[PA] = reinterpret_cast<plane2(*)[PA]>(lds + wave * kWaveBytes + DK_KC * PW * (int)sizeof(plane2));
+
+    // this wavefront's part of K, cut into equal chunks of at most DK_KC k-words
+    const int per_wave = (p.Kw + DK_WAVES - 1) / DK_WAVES;
+    const int kb = wave * per_wave;
+    const int ke = (kb + per_wave < p.Kw) ? kb + per_wave : p.Kw;
+    const int nchunks = (per_wave + DK_KC - 1) / DK_KC;
+    const int kc = (per_wave + nchunks - 1) / nchunks;
+
+    // Staging: a lane fetches two neighbouring k-words of one row per pass, eight lanes cover a row's
+    // DK_KC k-words (128 contiguous bytes), a pass covers eight rows.  Buffer loads: offsets at or beyond
+    // num_records return zero, which serves rows past M / N; k-words outside [k0, k1) are sent there.
+    constexpr uint32_t kOutOfRange = 0x80000000u;
+    constexpr int kRsrcFlags = 0x00020000;
+    constexpr int WPASS = BM / 8, APASS = BN / 8;
+    const int64_t wbase = (int64_t)row0 * p.Kw, abase = (int64_t)col0 * p.Kw;
+    const int64_t wleft = ((int64_t)p.M * p.Kw - wbase) * 8, aleft = ((int64_t)p.N * p.Kw - abase) * 8;
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<plane2*>(p.W + wbase), 0, (int)(wleft < 0x7FFFFFFFLL ? wleft : 0x7FFFFFFFLL), kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<plane2*>(p.A + abase), 0, (int)(aleft < 0x7FFFFFFFLL ? aleft : 0x7FFFFFFFLL), kRsrcFlags);
+    const int st_row = lane >> 3, st_kp = (lane & 7) * 2;
+    auto load2 = [](const __amdgpu_buffer_rsrc_t& r, uint32_t off) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+        plane2 o;
+        o.x = v[0];
+        o.y = v[1];
+        return o;
+    };
+    plane2 wreg[WPASS][2], areg[APASS][2];
+    auto fetch = [&](int k0) {
+        const int k1 = (k0 + kc < ke) ? k0 + kc : ke;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int kw = k0 + st_kp + h;
+            const bool ok = kw < k1;
+#pragma unroll
+            for (int i = 0; i < WPASS; ++i)
+                wreg[i][h] = load2(wrsrc, ok ? ((uint32_t)(st_row + 8 * i) * (uint32_t)p.Kw + (uint32_t)kw) * 8u : kOutOfRange);
+#pragma unroll
+            for (int i = 0; i < APASS; ++i)
+                areg[i][h] = load2(arsrc, ok ? ((uint32_t)(st_row + 8 * i) * (uint32_t)p.Kw + (uint32_t)kw) * 8u : kOutOfRange);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int i = 0; i < WPASS; ++i) Ws[st_kp + h][st_row + 8 * i] = wreg[i][h];
+#pragma unroll
+            for (int i = 0; i < APASS; ++i) As[st_kp + h][st_row + 8 * i] = areg[i][h];
+        }
+    };
+
+    Acc<OP> acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int c = 0; c < TN; ++c) acc[i][c].clear();
+    const int wrow = ly * 2, wcol = lx * 2;
+    auto read_frag = [&](int j, plane2 (&w)[TM], plane2 (&a)[TN]) {
+#pragma unroll
+        for (int q = 0; q < TM / 2; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4*>(&Ws[j][wrow + q * 16]);
+            w[2 * q].x = v.x; w[2 * q].y = v.y;
+            w[2 * q + 1].x = v.z; w[2 * q + 1].y = v.w;
+        }
+#pragma unroll
+        for (int q = 0; q < TN / 2; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4*>(&As[j][wcol + q * 16]);
+            a[2 * q].x = v.x; a[2 * q].y = v.y;
+            a[2 * q + 1].x = v.z; a[2 * q + 1].y = v.w;
+        }
+    };
+    // LDS operations of one wavefront execute in the order they are issued; the fences only keep the
+    // compiler from moving the reads of a chunk above the writes that fill it (other lanes' writes).
+    auto wave_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    if (kb < ke) {
+        fetch(kb);
+        for (int k0 = kb; k0 < ke; k0 += kc) {
+            wave_sync();                      // the previous chunk has been read
+            stage();
+            if (k0 + kc < ke) fetch(k0 + kc);  // in flight while this chunk is consumed
+            wave_sync();
+            const int jn = (k0 + kc < ke ? kc : ke - k0);
+            plane2 w[2][TM], a[2][TN];
+            read_frag(0, w[0], a[0]);
+#pragma unroll
+            for (int j = 0; j < DK_KC; ++j) {
+                if (j < jn) {   // wave-uniform
+                    if (j + 1 < DK_KC && j + 1 < jn) read_frag(j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+                    FATNN_VOP3_RUN_PHASE();
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    }
+
+    // ---- the eight partial sums meet: [wavefront][accumulator word][lane] --------------------------------
+    __syncthreads();   // every wavefront is done with its staging area (the sums reuse the space)
+    int32_t* const red = reinterpret_cast<int32_t*>(lds);
+    constexpr int kWaveWords = kWaveBytes / 4;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int c = 0; c < TN; ++c)
+#pragma unroll
+            for (int q = 0; q < Acc<OP>::kWords; ++q)
+                red[wave * kWaveWords + ((i * TN + c) * Acc<OP>::kWords + q) * 64 + lane] = acc[i][c].word(q);
+    __syncthreads();
+    // thread (wave, lane) finishes the accumulator pairs wave, wave + 8, ... of `lane`: outputs (m, n), (m, n + 1)
+    constexpr int kPairs = TM * TN / 2;
+    constexpr int kRounds = (kPairs + DK_WAVES - 1) / DK_WAVES;
+    const bool pair_c = p.ldc_n == 1 && (p.ldc_m & 1) == 0 && (reinterpret_cast<uintptr_t>(p.C) & 7) == 0;
+    const bool pair_f = p.ldf_n == 1 && (p.ldf_m & 1) == 0 && (reinterpret_cast<uintptr_t>(p.Cf) & 7) == 0;
+#pragma unroll
+    for (int pr = 0; pr < kRounds; ++pr) {
+        const int pidx = wave + pr * DK_WAVES;   // = i * (TN / 2) + c / 2
+        const int i = pidx / (TN / 2), c = (pidx % (TN / 2)) * 2;
+        const int m = row0 + wrow + (i >> 1) * 16 + (i & 1);
+        const int n = col0 + wcol + (c >> 1) * 16;
+        if (pidx < kPairs && m < p.M && n < p.N) {
+            Acc<OP> sum[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+#pragma unroll
+                for (int q = 0; q < Acc<OP>::kWords; ++q) {
+                    int32_t v = 0;
+#pragma unroll
+                    for (int w8 = 0; w8 < DK_WAVES; ++w8)
+                        v += red[w8 * kWaveWords + ((i * TN + c + e) * Acc<OP>::kWords + q) * 64 + lane];
+                    sum[e].word(q) = v;
+                }
+            int32_t rc = 0;
+            if (OP == OP_TERNARY) rc = p.cmul * p.rowc[m];
+            const int32_t v0 = finalize<OP>(sum[0], p, rc);
+            const int32_t v1 = finalize<OP>(sum[1], p, rc);
+            const bool two = n + 1 < p.N;
+            if (p.C != nullptr) {
+                int32_t* dst = p.C + ((int64_t)m * p.ldc_m + (int64_t)n * p.ldc_n);
+                if (pair_c && two) {
+                    typedef int32_t i32x2 __attribute__((ext_vector_type(2)));
+                    const i32x2 v = {v0, v1};
+                    *reinterpret_cast<i32x2*>(dst) = v;
+                } else {
+                    dst[0] = v0;
+                    if (two) dst[p.ldc_n] = v1;
+                }
+            }
+            if (p.Cf != nullptr) {
+                const float sc = p.scale[m];
+                float f0 = __fmul_rn(sc, (float)v0), f1 = __fmul_rn(sc, (float)v1);
+                if (p.bias != nullptr) {
+                    const float bs = p.bias[m];
+                    f0 = __fadd_rn(f0, bs);
+                    f1 = __fadd_rn(f1, bs);
+                }
+                float* dst = p.Cf + ((int64_t)m * p.ldf_m + (int64_t)n * p.ldf_n);
+                if (pair_f && two) {
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    const f32x2 v = {f0, f1};
+                    *reinterpret_cast<f32x2*>(dst) = v;
+                } else {
+                    dst[0] = f0;
+                    if (two) dst[p.ldf_n] = f1;
+                }
+            }
+        }
+    }
+}
+
+// Few columns and a long K (fully connected layers at batch 9-128): chosen where even the 32 x 32 tiles of
+// the problem number at most two per compute unit.  16-row tiles where 32-row tiles would leave compute
+// units without a workgroup.  Measured for 4096 x N x 4608: N = 17 / 32 / 64 / 128 in 7.2 / 6.9 / 9.7 /
+// 14.8 us against 17.9 / 17.6 / 17.8 / 20.3 us on the tiled kernel.  Returns 1 when the shape does not suit it.
+template <int OP>
+int launch_deepk(const GemmParams& p, hipStream_t stream) {
+    // (the three-accumulator uniform two-bit basis is not a fully connected layer's operator; it keeps the tiled kernel)
+    if constexpr (OP == OP_TWOBIT_UNIFORM) {
+        return 1;
+    } else {
+    if (p.is_conv || p.N > 128 || p.Kw < 64) return 1;
+    const int mode = tuning().gemm_deepk;   // 0 automatic, 1 always (where the shape fits), 2 never
+    if (mode == 2) return 1;
+    const int cus = compute_units();
+    const int64_t tiles_n = ((int64_t)p.N + DK_BN - 1) / DK_BN;
+    const int64_t t32 = (((int64_t)p.M + 31) / 32) * tiles_n;
+    if (mode == 0 && t32 > 2 * (int64_t)cus) return 1;
+    if (((int64_t)p.M + 15) / 16 * tiles_n > 0x7FFFFFF0LL) return 1;
+    const LaunchTiming t = take_launch_timing();
+    // (64-row tiles were measured too: never faster, 4096 x 128 x 4608 15.7 against 14.8 us)
+    if (t32 >= cus) {
+        const int tiles_m = (p.M + 31) / 32;
+        hipExtLaunchKernelGGL((deepk_gemm_kernel<OP, 4>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * DK_WAVES), 0,
+                              stream, t.start, t.stop, 0, p, tiles_m);
+    } else {
+        const int tiles_m = (p.M + 15) / 16;
+        hipExtLaunchKernelGGL((deepk_gemm_kernel<OP, 2>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * DK_WAVES), 0,
+                              stream, t.start, t.stop, 0, p, tiles_m);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+    }
+}
+
 template <int OP, int WM, int WN, int TM, int TN>
 int launch_shape(const GemmParams& p, hipStream_t stream) {
     constexpr int BM = WM * 8 * TM;
@@ -629,7 +873,9 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
     const int64_t wave_tiles = (((int64_t)p.M + WTM - 1) / WTM) * (((int64_t)p.N + WTN - 1) / WTN);
     if (wave_tiles >= 16 * 1024 && p.M > WTM) return launch_shape<OP, 2, 2, TM, TN>(p, stream);
     if (!p.is_conv) {
-        const int rc = launch_even_share<OP, TM / 2, TN / 2>(p, stream);
+        int rc = launch_deepk<OP>(p, stream);
+        if (rc <= 0) return rc;
+        rc = launch_even_share<OP, TM / 2, TN / 2>(p, stream);
         if (rc <= 0) return rc;
     }
     if (wave_tiles >= 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);

@@ -88,14 +88,12 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const GemmParams p) {
 
 }  // namespace
 
-// N <= 8 always; up to 16 columns (two chunks) for a long K while the tiled kernel would have fewer
-// workgroup tiles than compute units.  Measured for M = 4096, K = 4608: the tiled kernel takes 24-26 us for
-// any N <= 128 (a latency-bound K loop on 64 workgroups), this kernel 13 us at N = 16, but 24.5 us at
-// N = 32 and 46 us at N = 64, and with a short K most of its lanes idle.
+// Up to eight columns (measured for M = 4096, K = 4608: 4.7 us at N = 1, 7.7 us at N = 8).  More columns go
+// to the K-splitting kernel of the tiled family (7 us from N = 9 to 32), where this kernel needed 13 us at
+// N = 16, 24.5 us at N = 32 and 46 us at N = 64.
 bool skinny_supported(const GemmParams& p, int op) {
     if (op != OP_TERNARY || p.is_conv) return false;
-    if (p.N <= 8) return true;
-    return p.N <= 16 && p.Kw >= 128 && (int64_t)((p.M + 63) / 64) < 256;
+    return p.N <= 8;
 }
 
 int launch_skinny_gemm(const GemmParams& p, hipStream_t stream) {

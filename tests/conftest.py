@@ -35,4 +35,4 @@ def tuning():
     def set_(**kw):
         fatnn.set_tuning(**kw)
     yield set_
-    fatnn.set_tuning(conv_kernel=0, stream_wps=0, seven_pixel_groups=1, gemm_even_share=0)
+    fatnn.set_tuning(conv_kernel=0, stream_wps=0, seven_pixel_groups=1, gemm_even_share=0, gemm_deepk=0)

@@ -97,3 +97,50 @@ def test_even_share_twobit_and_binary_operators(tuning, basis):
     Cb = fatnn.binary_gemm(fatnn.pack_binary(dev(Bw)), fatnn.pack_binary(dev(Ba)), M, N, K + 37)
     assert np.array_equal(Cb.cpu().numpy(), oracle.binary_gemm(Bw, Ba))
     assert counters_are_zero(fatnn.gemm_workspace(DEV))
+
+
+# ----------------------------------------------------------------------------- few columns, long K
+@pytest.mark.parametrize("M,N,K,mode", [(4096, 17, 4608, 0), (4096, 32, 4608, 1), (4096, 64, 4608, 0),
+                                        (4096, 128, 4608, 1), (1000, 100, 9216, 0), (70, 33, 2048, 1),
+                                        (4096, 127, 4609, 0), (33, 128, 2049, 0), (512, 20, 65536, 1)])
+def test_deepk_kernel_matches_oracle(tuning, M, N, K, mode):
+    """Fully connected layers at batch 17-128 (Supplementary S1: a convolution whose filter covers the map)."""
+    tuning(gemm_deepk=1)          # the kernel itself, also where the automatic choice would take another
+    rnd = np.random.default_rng(M + 7 * N + K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    scale = rnd.uniform(0.5, 1.5, M).astype(np.float32)
+    bias = rnd.standard_normal(M).astype(np.float32)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    C, Cf = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, scale=dev(scale), bias=dev(bias))
+    want = oracle.ternary_gemm(Lw, La, mode)
+    assert np.array_equal(C.cpu().numpy(), want)
+    assert np.array_equal(Cf.cpu().numpy(), oracle.scale_epilogue(want, scale, bias, channel_is_row=True))
+    # odd output pitch (no paired stores) and the tiled kernel on the same operands
+    Cbig = torch.full((M, N + 3), -5, dtype=torch.int32, device=DEV)
+    fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, out=Cbig[:, :N])
+    assert np.array_equal(Cbig.cpu().numpy()[:, :N], want) and bool((Cbig[:, N:] == -5).all())
+    tuning(gemm_deepk=2)
+    C2, _ = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode)
+    assert torch.equal(C, C2)
+
+
+def test_deepk_kernel_twobit_and_binary_operators(tuning):
+    tuning(gemm_deepk=1)
+    rnd = np.random.default_rng(123)
+    M, N, K = 700, 50, 4000
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    want = oracle.ternary_gemm(Lw, La, 0)
+    C = fatnn.twobit_gemm(fatnn.pack_twobit(dev(CODE[Lw])), fatnn.pack_twobit(dev(CODE[La])), M, N, K, 0)
+    assert np.array_equal(C.cpu().numpy(), want)          # Eq. 2 on Table 1's codecs = the ternary product
+    Qw = rnd.integers(0, 4, size=(M, K), dtype=np.int8)
+    Qa = rnd.integers(0, 4, size=(N, K), dtype=np.int8)
+    for basis in (0, 1):
+        C = fatnn.twobit_gemm(fatnn.pack_twobit(dev(Qw)), fatnn.pack_twobit(dev(Qa)), M, N, K, basis)
+        assert np.array_equal(C.cpu().numpy(), oracle.twobit_gemm(Qw, Qa, basis))
+    Bw = rnd.integers(0, 2, size=(M, 2 * K + 5), dtype=np.int8)
+    Ba = rnd.integers(0, 2, size=(N, 2 * K + 5), dtype=np.int8)
+    Cb = fatnn.binary_gemm(fatnn.pack_binary(dev(Bw)), fatnn.pack_binary(dev(Ba)), M, N, 2 * K + 5)
+    assert np.array_equal(Cb.cpu().numpy(), oracle.binary_gemm(Bw, Ba))

@@ -78,12 +78,13 @@ def test_level_status_and_tuning_arguments(lib):
     assert lib.fatnn_level_status(0) == 0
     assert lib.fatnn_level_status(1) == -3 and lib.fatnn_level_status(1 << 40) == -3
     assert lib.fatnn_status_str(-3).decode() == "level outside {0,1,2}"
-    assert lib.fatnn_set_tuning(-1, -1, -1, -1) == 0            # keeps everything
-    assert lib.fatnn_set_tuning(2, 0, 1, 0) == -6
-    assert lib.fatnn_set_tuning(0, 9, 1, 0) == -6
-    assert lib.fatnn_set_tuning(0, 0, 3, 0) == -6
-    assert lib.fatnn_set_tuning(0, 0, 1, 10) == -6
-    assert lib.fatnn_set_tuning(0, 0, 1, 0) == 0
+    assert lib.fatnn_set_tuning(-1, -1, -1, -1, -1) == 0            # keeps everything
+    assert lib.fatnn_set_tuning(2, 0, 1, 0, 0) == -6
+    assert lib.fatnn_set_tuning(0, 9, 1, 0, 0) == -6
+    assert lib.fatnn_set_tuning(0, 0, 3, 0, 0) == -6
+    assert lib.fatnn_set_tuning(0, 0, 1, 10, 0) == -6
+    assert lib.fatnn_set_tuning(0, 0, 1, 0, 3) == -6
+    assert lib.fatnn_set_tuning(0, 0, 1, 0, 0) == 0
 
 
 def dims(*v):
