@@ -836,10 +836,15 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
     if (forced >= 1 && forced <= 8) {
         G = (int64_t)cus * forced;
     } else {
-        // Measured (512 x 3136 x 4609: 38.4 -> 34.9 us, 1536^2 x 4096: 46.9 -> 41.0 us, 2048^3 equal,
-        // 3072^3 and 256 x 12544 x 1152 slower): the even shares pay where the tiles would not give every
-        // compute unit four workgroups and K is long enough (a dozen stages) to carry the hand-over.
-        if (ntiles >= 4 * (int64_t)cus || nst < 12) return 1;
+        // Measured (1536^2 x 4096: 44.5 -> 40.3 us, 768^2 x 8192: 34.7 -> 29.9 us; 2048^3 equal; 3072^3,
+        // 256 x 12544 x 1152 and 512 x 3136 x 2304 slower): the even shares pay where the 64 x 64 tiles would
+        // not give every compute unit four workgroups and K is long enough (sixteen stages) to carry the
+        // hand-over.
+        const int64_t t32 = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
+        if (ntiles >= 4 * (int64_t)cus || nst < 16) return 1;
+        // between three and eight 32 x 32 tiles per compute unit the tile-per-workgroup launch is as good or
+        // better (512 x 3136 x 4609: 32.5 against 34.3 us; 1024^2 x 4096: 21.3 against 23.5 us)
+        if (t32 >= 3 * (int64_t)cus && t32 < 8 * (int64_t)cus) return 1;
         // four workgroups (= four wavefronts per SIMD) per compute unit, but at least four stages each
         G = (int64_t)cus * 4;
         if (G > units / 4) G = units / 4;

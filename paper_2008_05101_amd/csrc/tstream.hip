@@ -114,6 +114,11 @@ __global__ __launch_bounds__(256 * (CWT / CW)) void stream_conv_kernel(const Str
     static_assert(CWT % CW == 0, "the wavefronts of a row block split the channel words evenly");
     // hand-over of partial sums (KH > 1 only): [row block of the workgroup][group parity][pixel][lane]
     extern __shared__ int32_t handover[];
+    // Every wavefront starts at the priority its first groups run at: one that loaded its weights at the
+    // default (lowest) priority next to older wavefronts already in their groups was starved by them and
+    // reached its own first group up to 20 us late (measured), which left the SIMD with too few wavefronts
+    // at the end.
+    __builtin_amdgcn_s_setprio(3);
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int kh = KH > 1 ? wave_in_block % KH : 0;   // this wavefront's part of K
@@ -540,7 +545,12 @@ int launch_inst(StreamParams p, int64_t out_rows, int64_t Wo, hipStream_t stream
     if (ngroups <= 0 || ngroups > 0x7FFFFFF0LL) return -2;
     constexpr int KH = CWT / CW;                      // wavefronts per (row block, range)
     const int mblocks = (p.M + 63) / 64;
-    const int wpb = mblocks < 4 ? mblocks : 4;        // row blocks per workgroup
+    // Row blocks per workgroup: four wavefronts per workgroup whatever KH is.  (With four row blocks of
+    // four wavefronts each, a 512-channel workgroup filled a compute unit by itself, and the compute units
+    // whose workgroup had one group more than the others' worked a third longer: 35.7 against 26.7 us.
+    // Small workgroups let every compute unit hold some of both kinds.)
+    const int wpb_max = KH >= 4 ? 1 : (KH == 2 ? 2 : 4);
+    const int wpb = mblocks < wpb_max ? mblocks : wpb_max;
     const int waves = wpb * KH;
     static_assert(4 * KH <= kMaxWavesPerGroup, "occupancy cache too small for this workgroup");
     const size_t lds = KH > 1 ? (size_t)wpb * 2 * (KH - 1) * U * 64 * sizeof(int32_t) : 0;
