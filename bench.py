@@ -64,7 +64,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default depends on the workload)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed warm-up steps")
     ap.add_argument("--workload", default="cfg4",
-                    choices=["cfg4", "cfg2", "cfg3", "cfg5", "quantpack", "paper6", "peaks"])
+                    choices=["cfg4", "cfg2", "cfg3", "cfg5", "quantpack", "paper6", "peaks", "midgemm"])
+    ap.add_argument("--plain-input", action="store_true",
+                    help="cfg2 only: pack the activations in plain NHWC order, so that the convolution takes the "
+                         "LDS-tiled kernel's implicit-im2col front end instead of the streaming kernel")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -73,8 +76,8 @@ def parse_args():
     args = ap.parse_args()
     # Defaults long enough for the clocks to settle (a cfg2 step is 23 us: 200 steps were over before the GPU
     # had reached its sustained clock, and read 6 % slow), short enough to finish in seconds.
-    steps, warmup = {"cfg2": (4000, 1000), "cfg4": (100, 20), "cfg3": (200, 50), "cfg5": (50, 10),
-                     "quantpack": (100, 20), "paper6": (20, 3), "peaks": (3, 1)}[args.workload]
+    steps, warmup = {"cfg2": (4000, 1000), "cfg4": (100, 20), "cfg3": (200, 50), "cfg5": (600, 100),
+                     "quantpack": (300, 50), "paper6": (20, 3), "peaks": (3, 1), "midgemm": (20, 3)}[args.workload]
     if args.steps is None:
         args.steps = steps
     if args.warmup is None:
@@ -360,7 +363,8 @@ def side_workload(args, torch, fatnn, si, dev):
     """Workloads beyond the headline ones: the chained ResNet-18-shaped trunk (cfg3 as one pipeline) and
     the HBM-bound quantize-and-pack pass.  Same JSON shape, one line."""
     import numpy as np
-    settle_clocks(torch, lambda: torch.empty(1 << 26, dtype=torch.uint8, device=dev).fill_(1))
+    scratch = fatnn.probe_scratch(dev)
+    settle_clocks(torch, lambda: fatnn.probe_valu(fatnn.PROBE_PAIR_V, 4, 400, scratch))
     peaks = measure_peaks(torch, fatnn)
     if args.workload == "cfg3":
         from paper_2008_05101_amd import resnet_trunk as rt
@@ -502,6 +506,46 @@ def side_workload(args, torch, fatnn, si, dev):
         }
         print(json.dumps(line))
         return
+    if args.workload == "midgemm":
+        # GEMMs whose tiles do not fill the chip evenly: the ragged cfg5 GEMM, two square ones with a long K (even-share
+        # schedule) and fully connected layers at batch 16-128 (K-splitting kernel); each against the plain call
+        shapes = [(512, 3136, 4609), (1536, 1536, 4096), (768, 768, 8192), (4096, 16, 4608), (4096, 32, 4608),
+                  (4096, 64, 4608), (4096, 128, 4608)]
+        results = {}
+        tot_ms = tot_ops = 0.0
+        best = None
+        rng = torch.Generator(device=dev).manual_seed(20080510)
+        for (M, N, K) in shapes:
+            Wp = fatnn.pack_ternary(torch.randint(0, 3, (M, K), dtype=torch.int8, device=dev, generator=rng), fatnn.WEIGHT)
+            Ap = fatnn.pack_ternary(torch.randint(0, 3, (N, K), dtype=torch.int8, device=dev, generator=rng), fatnn.ACT)
+            C = torch.empty((M, N), dtype=torch.int32, device=dev)
+            # graph replays: the smallest of these kernels take less time than a Python call
+            ms = time_graph_ms(torch, lambda: fatnn.ternary_gemm(Wp, Ap, M, N, K, 0, out=C), args.steps)
+            fatnn.set_tuning(gemm_even_share=9, gemm_deepk=2)
+            ms_plain = time_graph_ms(torch, lambda: fatnn.ternary_gemm(Wp, Ap, M, N, K, 0, out=C, workspace=None),
+                                     args.steps)
+            fatnn.set_tuning(gemm_even_share=0, gemm_deepk=0)
+            ops = 2.0 * M * N * K
+            results[f"{M}x{N}x{K}"] = {"us": round(ms * 1e3, 2), "tops": round(ops / (ms * 1e-3) / 1e12, 1),
+                                       "tile_per_workgroup_us": round(ms_plain * 1e3, 2),
+                                       "speedup": round(ms_plain / ms, 3)}
+            tot_ms += ms
+            tot_ops += ops
+            if best is None or ops / ms > best[0]:
+                best = (ops / ms, f"{M}x{N}x{K}", ms)
+        line = {
+            "metric": "ternary GEMM Tops/s (2MNK) at 1 MI355X", "value": round(tot_ops / (tot_ms * 1e-3) / 1e12, 3),
+            "unit": "Tops/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(tot_ms, 5),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+            "config": {"workload": "midgemm: ternary GEMMs whose tiles do not fill 256 compute units evenly "
+                                   "(512x3136x4609, 1536^2x4096, 768^2x8192) and fully connected layers "
+                                   "4096xNx4608 at N = 16..128; operands already packed; value = all seven in a row"},
+            "roofline": alu_roofline(f"GEMM {best[1]}", best[0] / 1e9, best[2], peaks, None),
+            "cpu_baseline": None, "extra": results,
+        }
+        print(json.dumps(line))
+        return
     if args.workload == "cfg5":
         # ragged and low-K shapes, packing of the activations included in every step
         results = {}
@@ -630,7 +674,8 @@ def main():
         return
 
     if args.workload == "peaks":
-        settle_ms = settle_clocks(torch, lambda: torch.empty(1 << 26, dtype=torch.uint8, device=dev).fill_(1))
+        scratch = fatnn.probe_scratch(dev)
+        settle_ms = settle_clocks(torch, lambda: fatnn.probe_valu(fatnn.PROBE_PAIR_V, 4, 400, scratch))
         pk = measure_peaks(torch, fatnn, full=True)
         line = {"metric": "ternary VALU ceiling Tops/s (register-resident bitop3+bcnt pairs x 16 ops) at 1 MI355X",
                 "value": pk["ternary_peak_measured_tops"], "unit": "Tops/s", "n_gpus": 1, "steps": args.steps,
@@ -645,7 +690,7 @@ def main():
         print(json.dumps(line))
         return
 
-    if args.workload in ("cfg3", "cfg5", "quantpack", "paper6"):
+    if args.workload in ("cfg3", "cfg5", "quantpack", "paper6", "midgemm"):
         side_workload(args, torch, fatnn, si, dev)
         return
     extra = {}
@@ -658,7 +703,10 @@ def main():
         scale_d = torch.from_numpy(scale).to(dev)
         bias_d = torch.from_numpy(bias).to(dev)
         Wp = fatnn.pack_ternary(Lw_d, fatnn.WEIGHT, fatnn.OHWI)           # offline, once
-        Xp = torch.empty(fatnn.bordered_act_bytes(case.B, case.H, case.W, case.Cin, case.pad), dtype=torch.uint8,
+        plain = args.plain_input
+        x_layout = fatnn.X_PLAIN if plain else fatnn.X_BORDERED
+        Xp = torch.empty(fatnn.packed_bytes(fatnn.ACT, case.B * case.H * case.W, case.Cin) if plain else
+                         fatnn.bordered_act_bytes(case.B, case.H, case.W, case.Cin, case.pad), dtype=torch.uint8,
                          device=dev)
         Y = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.int32, device=dev)
         Yf = torch.empty((case.B, case.Ho, case.Wo, case.Cout), dtype=torch.float32, device=dev)
@@ -666,18 +714,23 @@ def main():
                      case.act_mode)
 
         def pack_step():
-            fatnn.pack_ternary_bordered(Lx_d, case.pad, case.act_mode, out=Xp)
+            if plain:
+                fatnn.pack_ternary(Lx_d, fatnn.ACT, fatnn.NHWC, out=Xp)
+            else:
+                fatnn.pack_ternary_bordered(Lx_d, case.pad, case.act_mode, out=Xp)
 
         def main_kernel():
-            fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y, scale=scale_d, bias=bias_d, out_f=Yf,
-                                 x_layout=fatnn.X_BORDERED)
+            fatnn.ternary_conv2d(Wp, Xp, *conv_args, out=Y, scale=scale_d, bias=bias_d, out_f=Yf, x_layout=x_layout)
 
         ops_per_step = 2.0 * case.macs()
         config = {"workload": "cfg2: 3x3 conv 128->128 @28x28, batch 32, stride 1, pad 1 as implicit GEMM "
                               "(M=128, N=25088, K=1152), ReLU-mode activations, int32 + fp32 scale/bias outputs; "
                               "step = pack activations + conv",
                   "M": case.M, "N": case.N, "K": case.K, "batch": case.B}
-        dominant = "stream_conv_kernel (ternary, weight-stationary implicit-GEMM conv)"
+        dominant = ("plane_gemm_kernel (ternary, LDS-tiled, implicit-im2col front end)" if plain else
+                    "stream_conv_kernel (ternary, weight-stationary implicit-GEMM conv)")
+        if plain:
+            config["workload"] += "; activations packed in plain NHWC order (--plain-input)"
     else:
         case = si.cfg4()
         Lw, La = case.make()
@@ -711,9 +764,14 @@ def main():
     vp = ctypes.c_void_p
     if args.workload == "cfg2":
         dims = (ctypes.c_int64 * 4)(case.B, case.H, case.W, case.Cin)
-        pack_args = (vp(Lx_d.data_ptr()), dims, case.pad, case.act_mode, vp(Xp.data_ptr()), Xp.numel(), None, vp(stream))
-        pack_fn = L.fatnn_pack_ternary_bordered
-        main_args = (vp(Wp.data_ptr()), vp(Xp.data_ptr()), fatnn.X_BORDERED, case.B, case.Cin, case.H, case.W, case.Cout,
+        if plain:
+            pack_args = (vp(Lx_d.data_ptr()), fatnn.NHWC, dims, fatnn.ACT, vp(Xp.data_ptr()), Xp.numel(), None, vp(stream))
+            pack_fn = L.fatnn_pack_ternary
+        else:
+            pack_args = (vp(Lx_d.data_ptr()), dims, case.pad, case.act_mode, vp(Xp.data_ptr()), Xp.numel(), None,
+                         vp(stream))
+            pack_fn = L.fatnn_pack_ternary_bordered
+        main_args = (vp(Wp.data_ptr()), vp(Xp.data_ptr()), x_layout, case.B, case.Cin, case.H, case.W, case.Cout,
                      case.R, case.S, case.stride, case.pad, case.act_mode, vp(Y.data_ptr()), vp(scale_d.data_ptr()),
                      vp(bias_d.data_ptr()), vp(Yf.data_ptr()), vp(stream))
         main_fn = L.fatnn_ternary_conv2d
@@ -762,7 +820,8 @@ def main():
     value = ops_per_step / (ms_per_step * 1e-3) / 1e12
 
     achieved = ops_per_step / (kernel_ms * 1e-3) / 1e12
-    roofline = alu_roofline(dominant, achieved, kernel_ms, peaks, measured_traffic_bytes(args.workload))
+    traffic_key = args.workload + ("_plain_input" if getattr(args, "plain_input", False) else "")
+    roofline = alu_roofline(dominant, achieved, kernel_ms, peaks, measured_traffic_bytes(traffic_key))
     extra["settle_ms_untimed"] = round(settle_ms, 1)
     extra["peaks_measured_in_this_run"] = peaks
 
@@ -776,7 +835,9 @@ def main():
             extra["step_ms_graph_replay"] = round(time_graph_ms(torch, step, 20), 5)
             extra["main_kernel_ms_graph_replay"] = round(time_graph_ms(torch, main_kernel, 20), 5)
             code = torch.tensor([0, 1, 3], dtype=torch.int8, device=dev)
-            if args.workload == "cfg2":
+            if args.workload == "cfg2" and args.plain_input:
+                pass
+            elif args.workload == "cfg2":
                 W2 = fatnn.pack_twobit(code[Lw_d.long()], fatnn.WEIGHT, fatnn.OHWI)
                 X2 = fatnn.pack_twobit_bordered(code[Lx_d.long()], case.pad)
                 t2 = time_kernel_ms(torch, lambda: fatnn.twobit_conv2d(W2, X2, *conv_args[:-1], out=Y,
