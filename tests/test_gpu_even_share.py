@@ -144,3 +144,25 @@ def test_deepk_kernel_twobit_and_binary_operators(tuning):
     Ba = rnd.integers(0, 2, size=(N, 2 * K + 5), dtype=np.int8)
     Cb = fatnn.binary_gemm(fatnn.pack_binary(dev(Bw)), fatnn.pack_binary(dev(Ba)), M, N, 2 * K + 5)
     assert np.array_equal(Cb.cpu().numpy(), oracle.binary_gemm(Bw, Ba))
+
+
+@pytest.mark.parametrize("per_cu,M,N,K", [(8, 4096, 32, 4608), (4, 512, 3136, 4609), (3, 640, 640, 16384)])
+def test_even_share_hand_over_is_stable_over_many_calls(tuning, per_cu, M, N, K):
+    """The hand-over between workgroups (write-through stores, counter, device-scope loads) has no ordering
+    slack: 300 calls in a row, many pieces per tile, every result equal to the oracle's."""
+    tuning(gemm_even_share=per_cu, gemm_deepk=2)
+    rnd = np.random.default_rng(per_cu + M)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    want = dev(oracle.ternary_gemm(Lw, La, 0))
+    ws = fatnn.gemm_workspace(DEV)
+    C = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    for _ in range(300):
+        C.fill_(-1)
+        fatnn.ternary_gemm(Wp, Ap, M, N, K, 0, out=C, workspace=ws)
+        bad += (C != want).sum()
+    assert int(bad.item()) == 0
+    assert counters_are_zero(ws)
