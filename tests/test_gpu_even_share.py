@@ -166,3 +166,23 @@ def test_even_share_hand_over_is_stable_over_many_calls(tuning, per_cu, M, N, K)
         bad += (C != want).sum()
     assert int(bad.item()) == 0
     assert counters_are_zero(ws)
+
+
+@pytest.mark.parametrize("N,deepk", [(5, 0), (20, 1), (33, 2)])
+def test_gemm_at_the_k_limit(tuning, N, deepk):
+    """K = 2^24, the largest supported: |C| reaches 2K = 2^25 in ReLU mode and stays exact in int32.  The three
+    column counts go to the matrix-vector kernel, the K-splitting kernel and the tiled kernel (even shares)."""
+    tuning(gemm_deepk=deepk)
+    K, M = 1 << 24, 3
+    rnd = np.random.default_rng(N)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    Lw[0] = 2                                             # all +1: closed forms below
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    La[0] = 2
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    for mode in (0, 1):
+        C, _ = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode)
+        C = C.cpu().numpy()
+        assert C[0, 0] == (K if mode == 0 else 2 * K)
+        assert np.array_equal(C, oracle.ternary_gemm(Lw, La, mode))

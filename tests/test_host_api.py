@@ -179,6 +179,48 @@ def test_gemm_argument_errors(lib):
     assert g(*a, 4, 4, (1 << 20) + 1, 1, FAKE, 4, None) == E_SIZE                     # 9K must fit int32
 
 
+def test_workspace_noalloc_and_probe_argument_errors(lib):
+    assert lib.fatnn_gemm_workspace_bytes() == 65536 + 1024 * 2 * 64 * 32 * 3 * 4
+    assert lib.fatnn_noalloc_scratch_bytes() == 65536 + 512 * 2 * 64 * 64 * 4
+    assert lib.fatnn_probe_scratch_bytes() >= 4096 + 256 * 8 * 256 * 4
+    big = lib.fatnn_gemm_workspace_bytes()
+    init = lib.fatnn_gemm_workspace_init
+    assert init(None, big, None) == E_NULL
+    assert init(FAKE + 4, big, None) == E_ALIGN
+    assert init(FAKE, 1000, None) == E_SIZE
+    f = lib.fatnn_ternary_gemm_ws
+    a = (FAKE, FAKE)
+    assert f(*a, 4, 4, 8, 0, FAKE, 4, None, None, None, 0, FAKE + 8, big, None) == E_ALIGN      # workspace alignment
+    assert f(*a, 4, 4, 0, 0, FAKE, 4, None, None, None, 0, FAKE, big, None) == E_SHAPE
+    assert f(None, None, 0, 4, 8, 0, None, 4, None, None, None, 0, None, 0, None) == OK
+    assert lib.fatnn_twobit_gemm_ws(*a, 4, 4, 8, 0, FAKE, 4, FAKE + 8, big, None) == E_ALIGN
+    assert lib.fatnn_binary_gemm_ws(*a, 4, 4, 8, FAKE, 4, FAKE + 8, big, None) == E_ALIGN
+    g = lib.fatnn_ternary_gemm_noalloc
+    assert g(*a, 4, 4, 0, 0, FAKE, 4, None, None, None, 0, None) == E_SHAPE
+    assert g(*a, 4, 4, 8, 3, FAKE, 4, None, None, None, 0, None) == E_UNSUP
+    assert g(*a, 64 * 129, 64 * 128, 64, 0, FAKE, 64 * 128, None, None, None, 0, None) == E_SIZE  # > 16384 tiles
+    assert g(*a, 4, 4, 8, 0, None, 4, None, None, None, 0, None) == E_NULL
+    assert g(*a, 4, 4, 8, 0, FAKE, 3, None, None, None, 0, None) == E_SHAPE
+    assert g(FAKE + 8, FAKE, 4, 4, 8, 0, FAKE, 4, None, None, None, 0, None) == E_ALIGN
+    assert g(None, None, 0, 4, 8, 0, None, 4, None, None, None, 0, None) == OK
+    pv = lib.fatnn_probe_valu
+    sb = lib.fatnn_probe_scratch_bytes()
+    assert pv(5, 4, 10, FAKE, sb, None, None) == E_UNSUP
+    assert pv(0, 0, 10, FAKE, sb, None, None) == E_SHAPE
+    assert pv(0, 9, 10, FAKE, sb, None, None) == E_SHAPE
+    assert pv(0, 4, 0, FAKE, sb, None, None) == E_SHAPE
+    assert pv(0, 4, 10, None, sb, None, None) == E_NULL
+    assert pv(0, 4, 10, FAKE + 4, sb, None, None) == E_ALIGN
+    assert pv(0, 4, 10, FAKE, 100, None, None) == E_SIZE
+    ph = lib.fatnn_probe_hbm
+    assert ph(3, FAKE, FAKE, 1 << 20, FAKE, sb, None) == E_UNSUP
+    assert ph(2, FAKE, FAKE, 24, FAKE, sb, None) == E_SHAPE
+    assert ph(0, None, None, 1 << 20, FAKE, sb, None) == E_NULL
+    assert ph(1, None, FAKE, 1 << 20, FAKE, sb, None) == E_NULL
+    assert ph(2, FAKE, FAKE + 8, 1 << 20, FAKE, sb, None) == E_ALIGN
+    assert ph(2, FAKE, FAKE, 1 << 20, FAKE, 64, None) == E_SIZE
+
+
 def test_binary_argument_errors(lib):
     f = lib.fatnn_pack_binary
     assert lib.fatnn_binary_packed_bytes(3, 65) == 3 * 2 * 8
