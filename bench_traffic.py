@@ -6,12 +6,12 @@ The two counters read in KiB per dispatch; how a KiB of theirs relates to a KiB 
 the same box with a plain copy of known size (`bench.py --calibrate-copy`: the library's 128-bit copy
 kernel over 256 MiB, so 262144 KiB read and 262144 KiB written per dispatch):
 
-    rocprofv3 --pmc FETCH_SIZE -d gpurun_out/cal_fetch -o p --output-format csv -- python3 bench.py --calibrate-copy
-    rocprofv3 --pmc WRITE_SIZE -d gpurun_out/cal_write -o p --output-format csv -- python3 bench.py --calibrate-copy
-    rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pmc4_fetch -o p --output-format csv -- python3 bench.py --workload cfg4 --steps 5 --warmup 1 --no-cpu --no-extra
-    rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pmc4_write -o p --output-format csv -- python3 bench.py --workload cfg4 --steps 5 --warmup 1 --no-cpu --no-extra
-    python3 bench_traffic.py --workload cfg4 --kernel plane_gemm_kernel --fetch gpurun_out/pmc4_fetch \\
-        --write gpurun_out/pmc4_write --cal-fetch gpurun_out/cal_fetch --cal-write gpurun_out/cal_write
+    rocprofv3 --pmc FETCH_SIZE -d out/cal_fetch -o p --output-format csv -- python3 bench.py --calibrate-copy
+    rocprofv3 --pmc WRITE_SIZE -d out/cal_write -o p --output-format csv -- python3 bench.py --calibrate-copy
+    rocprofv3 --pmc FETCH_SIZE -d out/cfg4_fetch -o p --output-format csv -- python3 bench.py --workload cfg4 --steps 5 --warmup 1 --no-cpu --no-extra
+    rocprofv3 --pmc WRITE_SIZE -d out/cfg4_write -o p --output-format csv -- python3 bench.py --workload cfg4 --steps 5 --warmup 1 --no-cpu --no-extra
+    python3 bench_traffic.py --workload cfg4 --kernel plane_gemm_kernel --fetch out/cfg4_fetch \\
+        --write out/cfg4_write --cal-fetch out/cal_fetch --cal-write out/cal_write
 
 It rewrites the row of that workload in profiles/hbm_traffic.md (a table; bench.py reads the last column).
 """
