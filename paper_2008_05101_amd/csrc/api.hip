@@ -300,6 +300,9 @@ int run_conv(const void* Wp, const void* Xp, int x_layout, int64_t B, int64_t Ci
     p.scale = scale; p.bias = bias;
     p.is_conv = 1;
     p.B = (int32_t)B; p.H = (int32_t)Hs; p.Wd = (int32_t)Ws; p.Cw = Cw;
+    p.cw_shift = -1;
+    for (int sh = 0; sh < 20; ++sh)
+        if ((1 << sh) == Cw) p.cw_shift = sh;
     p.Ho = (int32_t)cs.Ho; p.Wo = (int32_t)cs.Wo; p.R = R; p.S = S; p.stride = stride; p.pad = pad_s;
     // a padded tap is the value 0: level 1 = codec 01 in symmetric mode (and in the two-bit
     // ternary basis), level 0 = codec 00 in ReLU mode

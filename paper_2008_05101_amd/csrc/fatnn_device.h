@@ -76,6 +76,7 @@ struct GemmParams {
     // convolution front end (is_conv != 0)
     int32_t is_conv;
     int32_t B, H, Wd, Cw, Ho, Wo, R, S, stride, pad;
+    int32_t cw_shift;       // log2(Cw) when Cw is a power of two, else -1
     uint32_t pad_x, pad_y;  // plane words of a padded tap (value 0)
     // even-share schedule (GEMM only): device workspace whose first kEvenShareCounterBytes are zero, or null
     void* ws;

@@ -285,17 +285,19 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
 #pragma unroll
             for (int i = 0; i < LW; ++i) wreg[i] = load2(wrsrc, kok ? woff[i] + (uint32_t)kw * 8u : kOutOfRange);
             if (CONV) {
-                // k-word -> (filter tap, channel word); c is innermost in K
+                // k-word -> (filter tap, channel word); c is innermost in K.  No integer division: the
+                // channel-word count of the usual layers is a power of two, and a tap index below nine
+                // splits into row and column of a 3 x 3 filter with one multiply (S is 1 or 3).
                 const int kwc = kok ? kw : 0;
-                const int tap = kwc / p.Cw;
+                const int tap = p.cw_shift >= 0 ? (kwc >> p.cw_shift) : kwc / p.Cw;
                 const int cw = kwc - tap * p.Cw;
-                const int r = tap / p.S;
+                const int r = p.S == 1 ? tap : (tap * 11) >> 5;
                 const int s = tap - r * p.S;
 #pragma unroll
                 for (int i = 0; i < LA; ++i) {
                     const int hi = hi0[i] + r;
                     const int wi = wi0[i] + s;
-                    const bool inside = hi >= 0 && hi < p.H && wi >= 0 && wi < p.Wd;
+                    const bool inside = (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.Wd;
                     const uint32_t off = aoff[i] + (uint32_t)((hi * p.Wd + wi) * p.Cw + cw) * 8u;
                     plane2 v = load2(arsrc, (kok && inside) ? off : kOutOfRange);
                     // a padded tap is the value 0; only its low plane can be non-zero (codec 01)

@@ -590,7 +590,9 @@ constexpr int resident_cw(int R, int CWT, int ST, int U) {
     if (CWT >= 8) return 4;
     // 128 channels: pairs of two-word wavefronts pay with the seven-pixel groups and on the stride-2 layer
     // (chained trunk at batch 64: 31 -> 29.5 us, 20.9 -> 18.9 us); with groups of four at stride 1 (rows
-    // that are no multiple of seven) the single four-word wavefront is faster, 17.9 against 19.3 us
+    // that are no multiple of seven) the single four-word wavefront is faster, 17.9 against 19.3 us.
+    // (Measured again with the priorities of today: one four-word wavefront with the seven-pixel groups takes
+    // 17.2 against 15.0 us on the batch-32 layer and 15.5 against 13.9 us on the stride-2 layer.)
     if (CWT == 4 && (U == 7 || ST == 2)) return 2;
     return CWT;
 }
