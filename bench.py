@@ -193,7 +193,8 @@ def measure_peaks(torch, fatnn, full=False):
     out = {"valu_T_lane_instr_per_s": {}, "hbm_GBps": {}}
     kinds = [("pair_vgpr_operands", fatnn.PROBE_PAIR_V), ("pair_sgpr_data_word", fatnn.PROBE_PAIR_S)]
     if full:
-        kinds += [("bcnt_alone", fatnn.PROBE_BCNT), ("bitop3_alone", fatnn.PROBE_BITOP3), ("xor_alone", fatnn.PROBE_XOR)]
+        kinds += [("pair_operands_from_lds", fatnn.PROBE_PAIR_LDS), ("bcnt_alone", fatnn.PROBE_BCNT),
+                  ("bitop3_alone", fatnn.PROBE_BITOP3), ("xor_alone", fatnn.PROBE_XOR)]
     waves = (1, 2, 3, 4, 5, 6, 7, 8) if full else (2, 4, 8)
     fatnn.probe_valu(fatnn.PROBE_PAIR_V, 4, 200, scratch)      # first launch loads the code
     best_pair = 0.0

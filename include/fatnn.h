@@ -329,6 +329,8 @@ int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups, in
  *   kind            0 pair, all operands in vector registers (as the tiled GEMM kernel issues it)
  *                   1 pair with the data word in a scalar register (as the streaming conv kernel does)
  *                   2 popcount alone   3 logic instruction alone   4 plain two-input xor
+ *                   5 pair with its data words re-read from LDS, one 128-bit read per 16 pairs (the large
+ *                     GEMM tile's ratio), issued ahead of their use
  *   waves_per_simd  1..8;  iters >= 1 loop iterations of 128 instructions each
  *   scratch         device, 16-byte aligned, at least fatnn_probe_scratch_bytes() bytes; contents
  *                   are read as operand values (any bit pattern) and overwritten

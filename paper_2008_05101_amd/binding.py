@@ -187,7 +187,7 @@ def _ws(workspace, device) -> Optional[torch.Tensor]:
     return workspace
 
 
-PROBE_PAIR_V, PROBE_PAIR_S, PROBE_BCNT, PROBE_BITOP3, PROBE_XOR = 0, 1, 2, 3, 4
+PROBE_PAIR_V, PROBE_PAIR_S, PROBE_BCNT, PROBE_BITOP3, PROBE_XOR, PROBE_PAIR_LDS = 0, 1, 2, 3, 4, 5
 HBM_READ, HBM_WRITE, HBM_COPY = 0, 1, 2
 
 

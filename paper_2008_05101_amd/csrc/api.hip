@@ -748,7 +748,7 @@ static int probe_cu_count(int* cus) {
 
 int fatnn_probe_valu(int kind, int waves_per_simd, int iters, void* scratch, size_t scratch_bytes,
                      int64_t* lane_instr, void* stream) {
-    if (kind < 0 || kind > 4) return FATNN_ERR_UNSUPPORTED;
+    if (kind < 0 || kind > 5) return FATNN_ERR_UNSUPPORTED;
     if (waves_per_simd < 1 || waves_per_simd > 8 || iters < 1) return FATNN_ERR_SHAPE;
     if (scratch == nullptr) return FATNN_ERR_NULL;
     if (!aligned(scratch, 16)) return FATNN_ERR_ALIGN;

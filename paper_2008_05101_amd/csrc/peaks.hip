@@ -23,13 +23,16 @@ constexpr int kProbeWords = 8;                       // x words held in register
 constexpr int kProbeAccs = 8;                        // accumulators (chains)
 constexpr int kPairsPerIter = kProbeWords * kProbeAccs;
 
-enum : int { PROBE_PAIR_V = 0, PROBE_PAIR_S = 1, PROBE_BCNT = 2, PROBE_BITOP3 = 3, PROBE_XOR = 4 };
+enum : int { PROBE_PAIR_V = 0, PROBE_PAIR_S = 1, PROBE_BCNT = 2, PROBE_BITOP3 = 3, PROBE_XOR = 4, PROBE_PAIR_LDS = 5 };
 
 // KIND  PROBE_PAIR_V  logic (all-VGPR operands) feeding the popcount of the same accumulator chain,
 //                     the ordering the tiled GEMM kernel uses
 //       PROBE_PAIR_S  the same with the data word in an SGPR, as the column-streaming kernel issues it
 //       PROBE_BCNT    the popcount alone, PROBE_BITOP3 the logic instruction alone, PROBE_XOR a plain
 //                     two-input VOP2 (for reference)
+//       PROBE_PAIR_LDS the pair with its data words re-read from LDS at the large GEMM tile's ratio (one
+//                     128-bit read per 16 pairs, issued one half-iteration ahead of its use): what operand
+//                     delivery through LDS alone costs, without global loads, barriers or address arithmetic
 template <int KIND>
 __global__ __launch_bounds__(256) void valu_probe_kernel(const int iters, const uint32_t* __restrict__ seed,
                                                         int32_t* __restrict__ sink) {
@@ -45,6 +48,34 @@ __global__ __launch_bounds__(256) void valu_probe_kernel(const int iters, const 
 #pragma unroll
     for (int a = 0; a < kProbeAccs; ++a) acc[a] = 0;
     uint32_t t = 0;
+    if constexpr (KIND == PROBE_PAIR_LDS) {
+        __shared__ __attribute__((aligned(16))) uint32_t tile[256 * 4 * 2];
+        for (int i = 0; i < 8; ++i) tile[tid * 8 + i] = x[i];
+        __syncthreads();
+        // eight distinct 16-byte addresses per wavefront and read, as in the tile kernel's fragment reads
+        const uint4* src = reinterpret_cast<const uint4*>(tile) + (tid & 56);
+        uint4 nx0 = src[0], nx1 = src[1];
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const uint4 c0 = nx0, c1 = nx1;
+                nx0 = src[(2 * it + half) & 7];          // in flight while the 32 pairs below issue
+                nx1 = src[((2 * it + half) & 7) + 256];
+                const uint32_t xs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+                FATNN_VOP3_RUN_PHASE();
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+#pragma unroll
+                    for (int i = 0; i < kProbeWords; ++i) {
+                        asm volatile("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x48" : "=v"(t) : "v"(xs[i]), "v"(s), "v"(nm));
+                        asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc[half * 4 + a]) : "v"(t));
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        t ^= nx0.x ^ nx1.x;
+    } else
     for (int it = 0; it < iters; ++it) {
         FATNN_VOP3_RUN_PHASE();
 #pragma unroll
@@ -122,6 +153,7 @@ int launch_valu_probe(int kind, int blocks, int iters, const uint32_t* seed, int
         FATNN_PROBE_CASE(PROBE_BCNT)
         FATNN_PROBE_CASE(PROBE_BITOP3)
         FATNN_PROBE_CASE(PROBE_XOR)
+        FATNN_PROBE_CASE(PROBE_PAIR_LDS)
         default: return -3;
     }
 #undef FATNN_PROBE_CASE

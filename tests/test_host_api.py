@@ -205,7 +205,7 @@ def test_workspace_noalloc_and_probe_argument_errors(lib):
     assert g(None, None, 0, 4, 8, 0, None, 4, None, None, None, 0, None) == OK
     pv = lib.fatnn_probe_valu
     sb = lib.fatnn_probe_scratch_bytes()
-    assert pv(5, 4, 10, FAKE, sb, None, None) == E_UNSUP
+    assert pv(6, 4, 10, FAKE, sb, None, None) == E_UNSUP
     assert pv(0, 0, 10, FAKE, sb, None, None) == E_SHAPE
     assert pv(0, 9, 10, FAKE, sb, None, None) == E_SHAPE
     assert pv(0, 4, 0, FAKE, sb, None, None) == E_SHAPE
