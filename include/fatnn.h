@@ -336,7 +336,7 @@ int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups, in
  *                   are read as operand values (any bit pattern) and overwritten
  *   lane_instr      HOST pointer or NULL: receives the number of 32-bit lane-instructions the launch
  *                   executes (workgroups * 256 lanes * iters * 128)
- * fatnn_probe_hbm streams `bytes` (a multiple of 16) with 128-bit accesses: kind 0 reads src, 1 writes
+ * fatnn_probe_hbm streams `bytes` (a multiple of 16, below 4 GiB) with 128-bit accesses: kind 0 reads src, 1 writes
  * dst, 2 copies src to dst (bytes read + bytes written = 2 * bytes); the unused pointer may be NULL.
  */
 size_t fatnn_probe_scratch_bytes(void);

@@ -772,6 +772,7 @@ int fatnn_probe_hbm(int kind, void* dst, const void* src, size_t bytes, void* sc
                     void* stream) {
     if (kind < 0 || kind > 2) return FATNN_ERR_UNSUPPORTED;
     if (bytes == 0 || bytes % 16 != 0) return FATNN_ERR_SHAPE;
+    if (bytes > 0xFFFFFFF0ull) return FATNN_ERR_SIZE;   // 32-bit buffer offsets
     if ((kind != 1 && src == nullptr) || (kind != 0 && dst == nullptr) || scratch == nullptr) return FATNN_ERR_NULL;
     if (!aligned(src, 16) || !aligned(dst, 16) || !aligned(scratch, 16)) return FATNN_ERR_ALIGN;
     if (scratch_bytes < fatnn_probe_scratch_bytes()) return FATNN_ERR_SIZE;
