@@ -816,13 +816,17 @@ def main():
     if status != 0:
         raise RuntimeError("a library call failed inside the timed loop")
     ms_per_step = wall * 1e3 / args.steps
-    kernel_ms = sum(hev.elapsed_ms(2 * j, 2 * j + 1) for j in range(len(timed))) / len(timed)
+    kernel_times = sorted(hev.elapsed_ms(2 * j, 2 * j + 1) for j in range(len(timed)))
+    kernel_ms = sum(kernel_times) / len(kernel_times)
     hev.close()
     value = ops_per_step / (ms_per_step * 1e-3) / 1e12
 
     achieved = ops_per_step / (kernel_ms * 1e-3) / 1e12
     traffic_key = args.workload + ("_plain_input" if getattr(args, "plain_input", False) else "")
     roofline = alu_roofline(dominant, achieved, kernel_ms, peaks, measured_traffic_bytes(traffic_key))
+    roofline["kernel_ms_median"] = round(kernel_times[len(kernel_times) // 2], 5)
+    roofline["kernel_ms_min"] = round(kernel_times[0], 5)
+    roofline["kernel_launches_timed"] = len(kernel_times)
     extra["settle_ms_untimed"] = round(settle_ms, 1)
     extra["peaks_measured_in_this_run"] = peaks
 
