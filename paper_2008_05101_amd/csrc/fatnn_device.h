@@ -91,7 +91,7 @@ int launch_gemm(const GemmParams& p, int op, hipStream_t stream);
 // The ternary GEMM under the even-share schedule whatever its size, wgs_per_cu workgroups per compute unit
 // (fewer if the workspace in p is smaller).  Returns 1 if the workspace cannot serve the problem.
 int launch_ternary_gemm_even_share(const GemmParams& p, int wgs_per_cu, hipStream_t stream);
-bool skinny_supported(const GemmParams& p, int op);          // N <= 8 ternary GEMM (matrix-vector shaped)
+bool skinny_supported(const GemmParams& p, int op);          // ternary GEMM with a handful of columns (matrix-vector shaped)
 int launch_skinny_gemm(const GemmParams& p, hipStream_t stream);
 
 // Measurement hook (fatnn_time_next_launch): events that the next GEMM / convolution

@@ -548,7 +548,7 @@ int compute_units();
 // no barrier inside the K loop, the wavefronts run freely -- and the eight partial popcount sums of Eq. 3
 // meet in LDS once, at the end, where each thread finishes two neighbouring outputs.
 constexpr int DK_WAVES = 8;       // wavefronts per workgroup = parts of K
-constexpr int DK_KC = 16;         // k-words staged per chunk
+constexpr int DK_KC = 8;          // k-words staged per chunk
 constexpr int DK_BN = 32;         // columns per tile
 
 template <int OP, int TM>
@@ -578,19 +578,20 @@ __global__ __launch_bounds__(64 * DK_WAVES) void deepk_gemm_kernel(const GemmPar
     const int nchunks = (per_wave + DK_KC - 1) / DK_KC;
     const int kc = (per_wave + nchunks - 1) / nchunks;
 
-    // Staging: a lane fetches two neighbouring k-words of one row per pass, eight lanes cover a row's
-    // DK_KC k-words (128 contiguous bytes), a pass covers eight rows.  Buffer loads: offsets at or beyond
+    // Staging: a lane fetches two neighbouring k-words of one row per pass, four lanes cover a row's
+    // DK_KC k-words (64 contiguous bytes), a pass covers sixteen rows.  Buffer loads: offsets at or beyond
     // num_records return zero, which serves rows past M / N; k-words outside [k0, k1) are sent there.
+    // Two chunks are in flight (two register sets): the first wait pays the memory latency for both.
     constexpr uint32_t kOutOfRange = 0x80000000u;
     constexpr int kRsrcFlags = 0x00020000;
-    constexpr int WPASS = BM / 8, APASS = BN / 8;
+    constexpr int WPASS = BM / 16, APASS = BN / 16;
     const int64_t wbase = (int64_t)row0 * p.Kw, abase = (int64_t)col0 * p.Kw;
     const int64_t wleft = ((int64_t)p.M * p.Kw - wbase) * 8, aleft = ((int64_t)p.N * p.Kw - abase) * 8;
     const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<plane2*>(p.W + wbase), 0, (int)(wleft < 0x7FFFFFFFLL ? wleft : 0x7FFFFFFFLL), kRsrcFlags);
     const __amdgpu_buffer_rsrc_t arsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<plane2*>(p.A + abase), 0, (int)(aleft < 0x7FFFFFFFLL ? aleft : 0x7FFFFFFFLL), kRsrcFlags);
-    const int st_row = lane >> 3, st_kp = (lane & 7) * 2;
+    const int st_row = lane >> 2, st_kp = (lane & 3) * 2;
     auto load2 = [](const __amdgpu_buffer_rsrc_t& r, uint32_t off) {
         const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
         plane2 o;
@@ -598,8 +599,9 @@ __global__ __launch_bounds__(64 * DK_WAVES) void deepk_gemm_kernel(const GemmPar
         o.y = v[1];
         return o;
     };
-    plane2 wreg[WPASS][2], areg[APASS][2];
-    auto fetch = [&](int k0) {
+    plane2 wreg[2][WPASS][2], areg[2][APASS][2];
+    auto fetch = [&](int k0, auto set_tag) {
+        constexpr int set = decltype(set_tag)::value;
         const int k1 = (k0 + kc < ke) ? k0 + kc : ke;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -607,21 +609,26 @@ __global__ __launch_bounds__(64 * DK_WAVES) void deepk_gemm_kernel(const GemmPar
             const bool ok = kw < k1;
 #pragma unroll
             for (int i = 0; i < WPASS; ++i)
-                wreg[i][h] = load2(wrsrc, ok ? ((uint32_t)(st_row + 8 * i) * (uint32_t)p.Kw + (uint32_t)kw) * 8u : kOutOfRange);
+                wreg[set][i][h] =
+                    load2(wrsrc, ok ? ((uint32_t)(st_row + 16 * i) * (uint32_t)p.Kw + (uint32_t)kw) * 8u : kOutOfRange);
 #pragma unroll
             for (int i = 0; i < APASS; ++i)
-                areg[i][h] = load2(arsrc, ok ? ((uint32_t)(st_row + 8 * i) * (uint32_t)p.Kw + (uint32_t)kw) * 8u : kOutOfRange);
+                areg[set][i][h] =
+                    load2(arsrc, ok ? ((uint32_t)(st_row + 16 * i) * (uint32_t)p.Kw + (uint32_t)kw) * 8u : kOutOfRange);
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](auto set_tag) {
+        constexpr int set = decltype(set_tag)::value;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
 #pragma unroll
-            for (int i = 0; i < WPASS; ++i) Ws[st_kp + h][st_row + 8 * i] = wreg[i][h];
+            for (int i = 0; i < WPASS; ++i) Ws[st_kp + h][st_row + 16 * i] = wreg[set][i][h];
 #pragma unroll
-            for (int i = 0; i < APASS; ++i) As[st_kp + h][st_row + 8 * i] = areg[i][h];
+            for (int i = 0; i < APASS; ++i) As[st_kp + h][st_row + 16 * i] = areg[set][i][h];
         }
     };
+    constexpr std::integral_constant<int, 0> set0{};
+    constexpr std::integral_constant<int, 1> set1{};
 
     Acc<OP> acc[TM][TN];
 #pragma unroll
@@ -650,28 +657,38 @@ __global__ __launch_bounds__(64 * DK_WAVES) void deepk_gemm_kernel(const GemmPar
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
-    if (kb < ke) {
-        fetch(kb);
-        for (int k0 = kb; k0 < ke; k0 += kc) {
-            wave_sync();                      // the previous chunk has been read
-            stage();
-            if (k0 + kc < ke) fetch(k0 + kc);  // in flight while this chunk is consumed
-            wave_sync();
-            const int jn = (k0 + kc < ke ? kc : ke - k0);
-            plane2 w[2][TM], a[2][TN];
-            read_frag(0, w[0], a[0]);
+    auto compute = [&](int k0) {
+        const int jn = (k0 + kc < ke ? kc : ke - k0);
+        plane2 w[2][TM], a[2][TN];
+        read_frag(0, w[0], a[0]);
 #pragma unroll
-            for (int j = 0; j < DK_KC; ++j) {
-                if (j < jn) {   // wave-uniform
-                    if (j + 1 < DK_KC && j + 1 < jn) read_frag(j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
-                    FATNN_VOP3_RUN_PHASE();
+        for (int j = 0; j < DK_KC; ++j) {
+            if (j < jn) {   // wave-uniform
+                if (j + 1 < DK_KC && j + 1 < jn) read_frag(j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+                FATNN_VOP3_RUN_PHASE();
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                        for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+    };
+    if (kb < ke) {
+        fetch(kb, set0);
+        if (kb + kc < ke) fetch(kb + kc, set1);
+        for (int k0 = kb; k0 < ke; k0 += 2 * kc) {
+            wave_sync();                                  // the previous chunk has been read
+            stage(set0);
+            if (k0 + 2 * kc < ke) fetch(k0 + 2 * kc, set0);   // in flight while two chunks are consumed
+            wave_sync();
+            compute(k0);
+            if (k0 + kc >= ke) break;
+            wave_sync();
+            stage(set1);
+            if (k0 + 3 * kc < ke) fetch(k0 + 3 * kc, set1);
+            wave_sync();
+            compute(k0 + kc);
         }
     }
 
@@ -748,10 +765,10 @@ __global__ __launch_bounds__(64 * DK_WAVES) void deepk_gemm_kernel(const GemmPar
     }
 }
 
-// Few columns and a long K (fully connected layers at batch 9-128): chosen where even the 32 x 32 tiles of
+// Few columns and a long K (fully connected layers at batch 5-128): chosen where even the 32 x 32 tiles of
 // the problem number at most two per compute unit.  16-row tiles where 32-row tiles would leave compute
-// units without a workgroup.  Measured for 4096 x N x 4608: N = 17 / 32 / 64 / 128 in 7.2 / 6.9 / 9.7 /
-// 14.8 us against 17.9 / 17.6 / 17.8 / 20.3 us on the tiled kernel.  Returns 1 when the shape does not suit it.
+// units without a workgroup.  Measured for 4096 x N x 4608: N = 16 / 32 / 64 / 128 in 6.1 / 6.2 / 8.5 /
+// 13.0 us against 17.1 / 17.5 / 17.7 / 20.4 us on the tiled kernel.  Returns 1 when the shape does not suit it.
 template <int OP>
 int launch_deepk(const GemmParams& p, hipStream_t stream) {
     // (the three-accumulator uniform two-bit basis is not a fully connected layer's operator; it keeps the tiled kernel)
@@ -901,7 +918,8 @@ int launch_ternary_gemm_even_share(const GemmParams& p, int wgs_per_cu, hipStrea
 
 int launch_gemm(const GemmParams& p, int op, hipStream_t stream) {
     if (p.M == 0 || p.N == 0) return 0;
-    if (skinny_supported(p, op)) return launch_skinny_gemm(p, stream);
+    // (the measurement switch that forces the K-splitting kernel also forces it over the matrix-vector kernel)
+    if (skinny_supported(p, op) && tuning().gemm_deepk != 1) return launch_skinny_gemm(p, stream);
     switch (op) {
         case OP_TERNARY: return launch_op<OP_TERNARY, 8, 8>(p, stream);
         case OP_TWOBIT_TERNARY: return launch_op<OP_TWOBIT_TERNARY, 8, 8>(p, stream);

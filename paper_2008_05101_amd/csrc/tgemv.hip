@@ -88,12 +88,12 @@ __global__ __launch_bounds__(256) void skinny_gemm_kernel(const GemmParams p) {
 
 }  // namespace
 
-// Up to eight columns (measured for M = 4096, K = 4608: 4.7 us at N = 1, 7.7 us at N = 8).  More columns go
-// to the K-splitting kernel of the tiled family (7 us from N = 9 to 32), where this kernel needed 13 us at
-// N = 16, 24.5 us at N = 32 and 46 us at N = 64.
+// Up to four columns, and up to eight with a short K.  Measured for M = 4096, K = 4608: 3.7 / 4.4 / 5.5 / 7.6 us
+// at N = 1 / 2 / 4 / 8; the K-splitting kernel of the tiled family takes 6.1 us for any N up to 32 there (and
+// 18.5 against this kernel's 17.8 us at 1000 x 8 x 25088), so it serves five columns and more when K >= 2048.
 bool skinny_supported(const GemmParams& p, int op) {
     if (op != OP_TERNARY || p.is_conv) return false;
-    return p.N <= 8;
+    return p.N <= 4 || (p.N <= 8 && p.Kw < 64);
 }
 
 int launch_skinny_gemm(const GemmParams& p, hipStream_t stream) {

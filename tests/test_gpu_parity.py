@@ -206,7 +206,7 @@ def test_gemm_parity_very_long_k(M, N, K):
 @pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 7, 8, 9, 13, 16])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_skinny_gemm_parity(N, mode):
-    # (N above 8 takes the matrix-vector kernel, two column chunks, only with K >= 4096 and few row tiles)
+    # (the matrix-vector kernel serves N <= 4, and N <= 8 with K < 2048; the rest goes to the K-splitting or tiled kernel)
     rnd = np.random.default_rng(N * 3 + mode)
     for M, K in [(1, 1), (5, 33), (130, 4609), (1027, 200), (70, 8200)]:
         Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
