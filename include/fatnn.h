@@ -307,12 +307,14 @@ int fatnn_level_status(int64_t n_invalid_host);
  * Measurement switches (no paper passage: they serve the kernel comparisons in the report).
  * Process-wide, stored in atomics, read by every later launch; a negative argument keeps the
  * current value.  Their initial values come from the environment variables FATNN_CONV_KERNEL
- * (=tiled), FATNN_STREAM_WPS and FATNN_STREAM_U7, read once on first use.
+ * (=tiled), FATNN_STREAM_WPS, FATNN_STREAM_U7, FATNN_GEMM_EVEN_SHARE and FATNN_GEMM_DEEPK, read once on
+ * first use.
  *   conv_kernel         0 = automatic, 1 = convolutions always take the LDS-tiled kernel
  *   stream_wps          wavefronts per SIMD of the column-streaming kernel, 0 = planned, at most 8
  *   seven_pixel_groups  0 = off, 1 = by the size rule, 2 = wherever a kernel exists
  *   gemm_even_share     schedule of the *_gemm_ws calls: 0 = automatic, 1..8 = even shares with that many
- *                       workgroups per compute unit whatever the size, 9 = never
+ *                       workgroups per compute unit whatever the size, 9 = never, 10 = whole tiles plus a
+ *                       split remainder wherever the tile count is not a multiple of the compute units
  *   gemm_deepk          kernel for GEMMs with at most 128 columns and K >= 2048 (fully connected layers):
  *                       0 = automatic, 1 = wherever the shape fits, 2 = never
  * Results never depend on these, only the kernel and launch shape chosen.

@@ -131,15 +131,35 @@ __device__ __forceinline__ int32_t finalize<OP_TWOBIT_UNIFORM>(const Acc<OP_TWOB
 // workgroup and end) and adds the number of its stages to the tile's counter; the piece whose addition
 // completes the count collects the other slots and runs the epilogue, so nobody ever waits for anybody.
 // The counters must be zero at launch and are zero again when the kernel has finished.
+//
+// Variant "whole tiles plus a split remainder" (whole > 0): the first `whole` workgroups take one whole tile
+// each, as in the plain launch, and only the tiles that would form the last, partly filled round on the
+// compute units are cut into even shares for the remaining workgroups, which are the first in dispatch
+// order: a compute unit then runs q whole tiles and one piece instead of q or q + 1 tiles, and only the
+// few split tiles pay for a hand-over.
 struct StreamKArgs {
-    int32_t* partial;    // [G][2][tile accumulator words], written and read inside one launch
+    int32_t* partial;    // [G - whole][2][tile accumulator words], written and read inside one launch
     int32_t* counters;   // [ntiles]
     int32_t nst;         // K stages per tile
     int32_t units;       // ntiles * nst
+    int32_t whole;       // leading workgroups that own exactly one whole tile (0: even shares for all)
+    // The shares without a division in the kernel: the first `extra` sharing workgroups own base + 1 units,
+    // the others base; the two reciprocals only seed the search for the owner of a unit.
+    int32_t base, extra;
+    float inv_base1, inv_base;
 };
 
+// Fills in the share sizes for `groups` sharing workgroups (all of them, or those behind the whole tiles).
+inline void set_shares(StreamKArgs& sk, int64_t groups) {
+    const int64_t shared_units = (int64_t)sk.units - (int64_t)sk.whole * sk.nst;
+    sk.base = (int32_t)(shared_units / groups);
+    sk.extra = (int32_t)(shared_units % groups);
+    sk.inv_base1 = 1.0f / (float)(sk.base + 1);
+    sk.inv_base = sk.base > 0 ? 1.0f / (float)sk.base : 0.0f;
+}
+
 template <int OP, int WM, int WN, int TM, int TN, bool CONV, bool STREAMK>
-__global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
+__global__ __launch_bounds__(64 * WM * WN, (TM * TN <= 4 ? 8 : 2)) void plane_gemm_kernel(const GemmParams p, const int tiles_m,
                                                                         const int ntiles, const StreamKArgs sk) {
     constexpr int NT = 64 * WM * WN;
     constexpr int BM = WM * 8 * TM;
@@ -160,8 +180,17 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
     // logical indices (gridDim.x is a multiple of 8).
-    const int per_xcd = gridDim.x >> 3;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    // (With a split remainder the piece workgroups come first in dispatch order -- they are then resident
+    // from the start whatever the occupancy -- and take the logical indices behind the whole tiles; the
+    // runs per XCD are formed over the whole-tile workgroups, whose number is a multiple of 8 as well.)
+    int logical;
+    if (STREAMK && sk.whole > 0) {
+        const int pieces = (int)gridDim.x - sk.whole;
+        const int b = (int)blockIdx.x - pieces;
+        logical = b < 0 ? sk.whole + (int)blockIdx.x : (b & 7) * (sk.whole >> 3) + (b >> 3);
+    } else {
+        logical = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
+    }
     if (!STREAMK && logical >= ntiles) return;
     const int tiles_n = ntiles / tiles_m;
 
@@ -460,10 +489,26 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
         run_stages(0, nkt);
         epilogue();
     } else {
+        if (sk.whole > 0 && logical < sk.whole) {
+            // a whole tile of a split-remainder launch: the plain path, kept apart from the bookkeeping of
+            // the pieces below so that it runs with the plain kernel's registers
+            work_total = nkt;
+            locate_tile(logical);
+            run_stages(0, nkt);
+            epilogue();
+            return;
+        }
         constexpr int kTileWords = TM * TN * Acc<OP>::kWords * NT;   // accumulator words of a tile
-        const int64_t G = gridDim.x;
+        const int G = (int)gridDim.x;
         const int nst = sk.nst;
-        auto first_unit = [&](int64_t g) { return (int32_t)((g * (int64_t)sk.units) / G); };
+        // first unit of workgroup g: one tile each up to `whole`, even shares of the rest beyond it
+        // (all in 32 bits: the host keeps the number of units below 2^31)
+        const int whole = sk.whole;
+        const int whole_units = whole * nst;
+        auto first_unit = [&](int g) {
+            const int i = g - whole;
+            return g <= whole ? g * nst : whole_units + i * sk.base + (i < sk.extra ? i : sk.extra);
+        };
         const int u_begin = first_unit(logical), u_end = first_unit(logical + 1);
         if (u_begin >= u_end) return;
         work_total = u_end - u_begin;
@@ -495,7 +540,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
             // invalidated: a release / acquire fence pair around plain stores flushes or drops the XCD's
             // whole L2, operands included, and was measured four times slower than the plain kernel; adding
             // all pieces into one slot with atomic read-modify-writes suffered from their contention.
-            int32_t* const mine = sk.partial + ((int64_t)logical * 2 + (s0 == 0 ? 1 : 0)) * kTileWords + tid;
+            int32_t* const mine = sk.partial + (int64_t)((logical - whole) * 2 + (s0 == 0 ? 1 : 0)) * kTileWords + tid;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -515,14 +560,18 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void plane_gemm_kernel(const GemmP
             // leave the counter at zero for the next launch
             if (tid == 0) __hip_atomic_store(sk.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             // the other pieces of this tile: every workgroup whose range meets [t_begin, t_begin + nst)
-            int64_t g = ((int64_t)t_begin * G) / sk.units;
-            while (g > 0 && first_unit(g) > t_begin) --g;
+            // (the reciprocals give the owner of the tile's first unit to within a few; the two loops settle it)
+            const int u_rel = t_begin - whole_units, knee = sk.extra * (sk.base + 1);
+            int g = u_rel < knee ? (int)((float)u_rel * sk.inv_base1)
+                                 : sk.extra + (int)((float)(u_rel - knee) * sk.inv_base);
+            g = whole + (g < 0 ? 0 : (g > G - whole - 1 ? G - whole - 1 : g));
+            while (g > whole && first_unit(g) > t_begin) --g;
             while (first_unit(g + 1) <= t_begin) ++g;
             for (; g < G && first_unit(g) < t_begin + nst; ++g) {
                 if (g == logical) continue;
                 if (first_unit(g + 1) <= first_unit(g)) continue;   // a workgroup without units
                 const int slot = first_unit(g) > t_begin ? 0 : 1;
-                const int32_t* const theirs = sk.partial + (g * 2 + slot) * kTileWords + tid;
+                const int32_t* const theirs = sk.partial + (int64_t)((g - whole) * 2 + slot) * kTileWords + tid;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -848,7 +897,7 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
     const int64_t units = ntiles * nst;
     if (ntiles > kEvenShareCounterBytes / 4 || units >= 0x7FFFFFFFLL) return 1;
     const int forced = always_per_cu > 0 ? always_per_cu : tuning().gemm_even_share;
-    if (forced == 9) return 1;
+    if (forced == 9 || forced == 10) return 1;
     const int cus = compute_units();
     const int64_t fit = ((int64_t)p.ws_bytes - kEvenShareCounterBytes) / (2 * kTileBytes);
     int64_t G;
@@ -877,9 +926,62 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
     sk.partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.ws) + kEvenShareCounterBytes);
     sk.nst = nst;
     sk.units = (int32_t)units;
+    set_shares(sk, G);
     const LaunchTiming t = take_launch_timing();
     hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false, true>), dim3((unsigned)G), dim3(NT), 0, stream,
                           t.start, t.stop, 0, p, tiles_m, (int)ntiles, sk);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Whole tiles plus a split remainder (see StreamKArgs): for tile counts of q * CUs + r with a small q, where
+// the plain launch leaves r compute units with q + 1 tiles and the others with q.  The q * CUs leading tiles
+// go one to a workgroup; the r remaining tiles are cut into one even share per compute unit.
+// Returns 0 = launched, 1 = not applicable, -1 = launch error.
+template <int OP, int TM, int TN>
+int launch_split_remainder(const GemmParams& p, hipStream_t stream) {
+    constexpr int WM = 2, WN = 2, NT = 256;
+    constexpr int BM = WM * 8 * TM, BN = WN * 8 * TN;
+    constexpr int64_t kTileBytes = (int64_t)TM * TN * Acc<OP>::kWords * NT * 4;
+    if (p.ws == nullptr || p.ws_bytes <= (size_t)kEvenShareCounterBytes) return 1;
+    const int forced = tuning().gemm_even_share;
+    if (forced != 0 && forced != 10) return 1;
+    const int tiles_m = (p.M + BM - 1) / BM;
+    const int64_t ntiles = (int64_t)tiles_m * (((int64_t)p.N + BN - 1) / BN);
+    const int nst = (p.Kw + KT - 1) / KT;
+    if (ntiles > kEvenShareCounterBytes / 4 || ntiles * nst >= 0x7FFFFFFFLL) return 1;
+    const int cus = compute_units();
+    const int64_t q = ntiles / cus, r = ntiles - q * cus;
+    // Measured on 256 x N x K with N chosen for q = 1..7 and r = 16..192 (times in us, plain launch -> this one):
+    // K = 9216: q >= 2, r <= 128: 38.5 -> 36.0, 48.2 -> 44.2, 68.3 -> 63.3 (5-8 % less), r = 192: 1-3 % less;
+    // K = 4608: the same 4-7 %; K = 2304: 1-6 % less from q = 5 on with r <= 64, 5-15 % more for q <= 3;
+    // K = 1152: 0-35 % more.  The hand-over of the split tiles has to hide behind at least q tiles of work.
+    // At most eight workgroups of these tiles are resident per compute unit, hence q <= 7.
+    if (r == 0 || q < 1) return 1;
+    if (forced == 0) {
+        if (q < 2 || q > 7) return 1;
+        if (nst >= 16) {
+            if (r > cus / 2) return 1;
+        } else if (nst >= 8) {
+            if (q < 5 || r > cus / 4) return 1;
+        } else {
+            return 1;
+        }
+    }
+    int64_t pieces = cus;
+    if (pieces > r * nst / 2) pieces = (r * nst / 2) & ~(int64_t)7;
+    const int64_t fit = ((int64_t)p.ws_bytes - kEvenShareCounterBytes) / (2 * kTileBytes);
+    if (pieces > fit) pieces = fit & ~(int64_t)7;
+    if (pieces < 8 || (q * cus) % 8 != 0) return 1;
+    StreamKArgs sk{};
+    sk.counters = reinterpret_cast<int32_t*>(p.ws);
+    sk.partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.ws) + kEvenShareCounterBytes);
+    sk.nst = nst;
+    sk.units = (int32_t)(ntiles * nst);
+    sk.whole = (int32_t)(q * cus);
+    set_shares(sk, pieces);
+    const LaunchTiming t = take_launch_timing();
+    hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false, true>), dim3((unsigned)(sk.whole + pieces)),
+                          dim3(NT), 0, stream, t.start, t.stop, 0, p, tiles_m, (int)ntiles, sk);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -906,6 +1008,10 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
         if (rc <= 0) return rc;
     }
     if (wave_tiles >= 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
+    if (!p.is_conv) {
+        const int rc = launch_split_remainder<OP, 2, 2>(p, stream);
+        if (rc <= 0) return rc;
+    }
     return launch_shape<OP, 2, 2, 2, 2>(p, stream);
 }
 

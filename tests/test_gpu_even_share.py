@@ -1,4 +1,5 @@
-"""The even-share ("stream-K") schedule of the tiled GEMM against the CPU oracle, bit-exact: every
+"""The even-share ("stream-K") schedule of the tiled GEMM, and its variant that splits only the remainder
+of the tile count over the compute units, against the CPU oracle, bit-exact: every
 workgroups-per-compute-unit setting, shapes whose tiles are cut between two workgroups and shapes whose
 tiles are shared by many, ragged M / N / K, all operators, the fp32 epilogue, small workspaces, and
 repeated calls on one workspace (the tile counters must come back to zero)."""
@@ -99,6 +100,66 @@ def test_even_share_twobit_and_binary_operators(tuning, basis):
     assert counters_are_zero(fatnn.gemm_workspace(DEV))
 
 
+# ----------------------------------------------------------------------------- whole tiles + split remainder
+@pytest.mark.parametrize("M,N,K,mode", [(512, 3136, 4609, 0),      # 1568 tiles = 6 per compute unit + 32 (automatic choice)
+                                        (416, 3200, 2304, 1),      # 1300 = 5 x 256 + 20
+                                        (320, 1000, 2500, 0),      # 320 = 256 + 64, pieces of 2.5 stages
+                                        (290, 900, 300, 1),        # two stages per tile: 32 pieces only
+                                        (32, 8224, 4096, 0),       # 257 tiles: one tile split eight ways
+                                        (200, 1337, 2000, 1),      # ragged M and N
+                                        (1024, 2080, 1024, 0)])    # 2080 = 8 x 256 + 32: nine workgroups per unit
+def test_split_remainder_matches_oracle(tuning, M, N, K, mode):
+    rnd = np.random.default_rng(M + 5 * N + K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    scale = rnd.uniform(0.5, 1.5, M).astype(np.float32)
+    bias = rnd.standard_normal(M).astype(np.float32)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    ws = fatnn.gemm_workspace(DEV)
+    want = oracle.ternary_gemm(Lw, La, mode)
+    wantf = oracle.scale_epilogue(want, scale, bias, channel_is_row=True)
+    for setting in (10, 0):                  # forced wherever there is a remainder, then the automatic choice
+        tuning(gemm_even_share=setting, gemm_deepk=2)
+        for _ in range(2):                   # the second call finds the counters as the first left them
+            C, Cf = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, scale=dev(scale), bias=dev(bias), workspace=ws)
+            assert np.array_equal(C.cpu().numpy(), want)
+            assert np.array_equal(Cf.cpu().numpy(), wantf)
+            assert counters_are_zero(ws)
+
+
+@pytest.mark.parametrize("nbytes", [65536 + 8 * 2 * 4096, 65536 + 50 * 2 * 4096, 65536 + 2 * 4096])
+def test_split_remainder_small_workspaces(tuning, nbytes):
+    """A workspace with room for 8 or 48 pieces limits the split; one too small for 8 sends the call to the
+    plain launch."""
+    tuning(gemm_even_share=10, gemm_deepk=2)
+    rnd = np.random.default_rng(nbytes)
+    M, N, K = 320, 1000, 2500
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    ws = fatnn.gemm_workspace(DEV, nbytes)
+    C, _ = fatnn.ternary_gemm(fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT), fatnn.pack_ternary(dev(La), fatnn.ACT),
+                              M, N, K, 0, workspace=ws)
+    assert np.array_equal(C.cpu().numpy(), oracle.ternary_gemm(Lw, La, 0))
+    assert counters_are_zero(ws)
+
+
+def test_split_remainder_twobit_and_binary_operators(tuning):
+    tuning(gemm_even_share=10, gemm_deepk=2)
+    rnd = np.random.default_rng(1010)
+    M, N, K = 320, 1000, 1500
+    Qw = rnd.integers(0, 4, size=(M, K), dtype=np.int8)
+    Qa = rnd.integers(0, 4, size=(N, K), dtype=np.int8)
+    for basis in (0, 1):
+        C = fatnn.twobit_gemm(fatnn.pack_twobit(dev(Qw)), fatnn.pack_twobit(dev(Qa)), M, N, K, basis)
+        assert np.array_equal(C.cpu().numpy(), oracle.twobit_gemm(Qw, Qa, basis))
+    Bw = rnd.integers(0, 2, size=(M, 2 * K + 5), dtype=np.int8)
+    Ba = rnd.integers(0, 2, size=(N, 2 * K + 5), dtype=np.int8)
+    Cb = fatnn.binary_gemm(fatnn.pack_binary(dev(Bw)), fatnn.pack_binary(dev(Ba)), M, N, 2 * K + 5)
+    assert np.array_equal(Cb.cpu().numpy(), oracle.binary_gemm(Bw, Ba))
+    assert counters_are_zero(fatnn.gemm_workspace(DEV))
+
+
 # ----------------------------------------------------------------------------- few columns, long K
 @pytest.mark.parametrize("M,N,K,mode", [(4096, 17, 4608, 0), (4096, 32, 4608, 1), (4096, 64, 4608, 0),
                                         (4096, 128, 4608, 1), (1000, 100, 9216, 0), (70, 33, 2048, 1),
@@ -146,7 +207,8 @@ def test_deepk_kernel_twobit_and_binary_operators(tuning):
     assert np.array_equal(Cb.cpu().numpy(), oracle.binary_gemm(Bw, Ba))
 
 
-@pytest.mark.parametrize("per_cu,M,N,K", [(8, 4096, 32, 4608), (4, 512, 3136, 4609), (3, 640, 640, 16384)])
+@pytest.mark.parametrize("per_cu,M,N,K", [(8, 4096, 32, 4608), (4, 512, 3136, 4609), (3, 640, 640, 16384),
+                                          (10, 512, 3136, 4609), (10, 32, 8224, 8192)])
 def test_even_share_hand_over_is_stable_over_many_calls(tuning, per_cu, M, N, K):
     """The hand-over between workgroups (write-through stores, counter, device-scope loads) has no ordering
     slack: 300 calls in a row, many pieces per tile, every result equal to the oracle's."""
