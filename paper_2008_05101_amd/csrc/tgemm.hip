@@ -904,17 +904,33 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
     if (forced >= 1 && forced <= 8) {
         G = (int64_t)cus * forced;
     } else {
-        // Measured (1536^2 x 4096: 44.5 -> 40.3 us, 768^2 x 8192: 34.7 -> 29.9 us; 2048^3 equal; 3072^3,
-        // 256 x 12544 x 1152 and 512 x 3136 x 2304 slower): the even shares pay where the 64 x 64 tiles would
-        // not give every compute unit four workgroups and K is long enough (sixteen stages) to carry the
-        // hand-over.
+        // Measured (1536^2 x 4096: 44.5 -> 40.8 us, 768^2 x 8192: 34.7 -> 27.9 us, 256^2 x 32768: 112 -> 32 us;
+        // 2048^3 equal; 3072^3, 256 x 12544 x 1152 and 512 x 3136 x 2304 slower): the even shares pay where the
+        // 64 x 64 tiles would not give every compute unit four workgroups and K is long enough (sixteen
+        // stages) to carry the hand-over.
         const int64_t t32 = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
         if (ntiles >= 4 * (int64_t)cus || nst < 16) return 1;
-        // between three and eight 32 x 32 tiles per compute unit the tile-per-workgroup launch is as good or
-        // better (512 x 3136 x 4609: 32.5 against 34.3 us; 1024^2 x 4096: 21.3 against 23.5 us)
-        if (t32 >= 3 * (int64_t)cus && t32 < 8 * (int64_t)cus) return 1;
-        // four workgroups (= four wavefronts per SIMD) per compute unit, but at least four stages each
-        G = (int64_t)cus * 4;
+        // From two to eight 32 x 32 tiles per compute unit the tile-per-workgroup launch (all tiles resident
+        // at once) is as good or better (1024^2 x 4096: 21.4 against 23.9 us, 768^2 x 4096: 19.3 against 19.9)
+        // until K reaches 32 stages (1024^2 x 8192: 38.9 -> 37.1 us).
+        if (t32 >= 2 * (int64_t)cus && t32 < 8 * (int64_t)cus && nst < 32) return 1;
+        // Beyond eight per unit that launch needs a second round of workgroups; the even shares win where that
+        // round is thin (1536^2 x 4096, one tile per unit left: 44.5 -> 40.8 us) and lose where it is well
+        // filled (1792^2 x 4096, 4.25 left: 52.4 against 54.3 us; 4096 x 512 x 4608, none left: 36.8 against 39.0).
+        if (t32 >= 8 * (int64_t)cus) {
+            const int64_t left = t32 % (8 * (int64_t)cus);
+            if (left == 0 || left > 3 * (int64_t)cus) return 1;
+        }
+        // About eight stages per workgroup, in whole multiples of the compute units (every unit then runs the
+        // same number of equal shares), two to four per unit -- but never more than sixteen pieces per tile
+        // nor fewer than four stages per piece.  Measured with 1 / 2 / 3 / 4 per unit: 256^2 x 32768 (16 tiles)
+        // 31.8 / 39.2 / 55.0 / 61.5 us, 512^2 x 16384 36.6 / 28.5 / 31.5 / 34.5, 768^2 x 8192 41.0 / 29.7 /
+        // 27.7 / 30.3, 333 x 777 x 5555 23.2 / 20.0 / 21.6 / 26.2, 1024^2 x 8192 61.0 / 40.9 / 39.3 / 36.6: the
+        // partial sums of a tile cut into many short pieces all pass through the one workgroup that finishes it.
+        int64_t per_cu = (units + 8 * (int64_t)cus - 1) / (8 * (int64_t)cus);
+        per_cu = per_cu < 2 ? 2 : (per_cu > 4 ? 4 : per_cu);
+        G = (int64_t)cus * per_cu;
+        if (G > 16 * ntiles) G = 16 * ntiles;
         if (G > units / 4) G = units / 4;
     }
     if (G > units) G = units;
@@ -1004,14 +1020,24 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
     if (!p.is_conv) {
         int rc = launch_deepk<OP>(p, stream);
         if (rc <= 0) return rc;
+        // Three to eight 32 x 32 tiles per compute unit: splitting only the remainder beats the even shares
+        // of 64 x 64 tiles where both apply (1280^2 x 8192: 50.8 against 54.8 us); with fewer tiles the even
+        // shares come first (256 x 2112 x 9216: 29.8 against 36.0 us).
+        const int64_t t32 = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
+        const int64_t cus = compute_units();
+        const bool split_first = t32 >= 3 * cus && t32 < 8 * cus;
+        if (split_first) {
+            rc = launch_split_remainder<OP, 2, 2>(p, stream);
+            if (rc <= 0) return rc;
+        }
         rc = launch_even_share<OP, TM / 2, TN / 2>(p, stream);
         if (rc <= 0) return rc;
+        if (!split_first && wave_tiles < 1024) {
+            rc = launch_split_remainder<OP, 2, 2>(p, stream);
+            if (rc <= 0) return rc;
+        }
     }
     if (wave_tiles >= 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
-    if (!p.is_conv) {
-        const int rc = launch_split_remainder<OP, 2, 2>(p, stream);
-        if (rc <= 0) return rc;
-    }
     return launch_shape<OP, 2, 2, 2, 2>(p, stream);
 }
 
