@@ -1006,9 +1006,11 @@ int launch_split_remainder(const GemmParams& p, hipStream_t stream) {
 // SIMD) up to 8192^3 and beats it below about 16 K wavefront tiles of 64 x 64, where tile quantisation
 // over 256 CUs matters; the large tile keeps a few per cent on very large problems with a shallow K
 // (fewer operand re-reads).  Below that size, and given a workspace, the 64 x 64 tile runs under the
-// even-share schedule, which has no tile quantisation at all.  Without a workspace: below about a thousand
-// 64 x 64 wavefront tiles the 32 x 32 tile (2 x 2 accumulators) puts four times as many wavefronts to work
-// (4096 x 64 x 4608: 25 -> 18 us, 1536^2 x 4096: 53 -> 41 us) but reads LDS once per 8 instruction pairs.
+// even-share schedule, which has no tile quantisation at all, or the 32 x 32 tile runs with only the
+// remainder of its tile count split (launch_even_share and launch_split_remainder say where each pays).
+// Otherwise: below about a thousand 64 x 64 wavefront tiles the 32 x 32 tile (2 x 2 accumulators) puts four
+// times as many wavefronts to work (4096 x 64 x 4608: 25 -> 18 us, 1536^2 x 4096: 53 -> 41 us) but reads LDS
+// once per 8 instruction pairs.
 template <int OP, int TM, int TN>
 int launch_op(const GemmParams& p, hipStream_t stream) {
     constexpr int WTM = 8 * TM, WTN = 8 * TN;
