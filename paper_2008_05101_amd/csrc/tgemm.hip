@@ -220,13 +220,18 @@ __global__ __launch_bounds__(64 * WM * WN, (TM * TN <= 4 ? 8 : 2)) void plane_ge
     // (Not for the 128 x 128 tile: its workgroups come in several rounds per compute unit, and 4096^3 was
     // measured 3.6 % slower with it.)
     constexpr bool kPaced = TM * TN <= 16;
-    int work_done = 0, work_total = 1;
+    // (work_mark[k] = the first stage at which k quarters of the work are done: the four levels without a
+    // division per stage)
+    int work_done = 0, work_mark[3] = {1, 1, 1};
+    auto set_work = [&](int total) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) work_mark[k] = ((k + 1) * total + 3) >> 2;
+    };
     auto pace = [&]() {
         if constexpr (!kPaced) return;
-        const int q = (4 * work_done) / work_total;
-        if (q <= 0) __builtin_amdgcn_s_setprio(3);
-        else if (q == 1) __builtin_amdgcn_s_setprio(2);
-        else if (q == 2) __builtin_amdgcn_s_setprio(1);
+        if (work_done < work_mark[0]) __builtin_amdgcn_s_setprio(3);
+        else if (work_done < work_mark[1]) __builtin_amdgcn_s_setprio(2);
+        else if (work_done < work_mark[2]) __builtin_amdgcn_s_setprio(1);
         else __builtin_amdgcn_s_setprio(0);
         ++work_done;
     };
@@ -371,25 +376,40 @@ __global__ __launch_bounds__(64 * WM * WN, (TM * TN <= 4 ? 8 : 2)) void plane_ge
         // One stage of the K loop from LDS buffer buf.  Fragments of k-word j+1 are read from LDS
         // while k-word j is consumed.  The scheduling fences keep the compiler from hoisting every
         // LDS read of the stage to its top (which needs more registers than there are).
+        auto compute_words = [&](int buf, int jn, auto full_tag) {
+            constexpr bool kFull = decltype(full_tag)::value;   // all KT k-words exist: no per-word test
+            plane2 w[2][TM], a[2][TN];
+            read_frag(buf, 0, w[0], a[0]);
+#pragma unroll
+            for (int j = 0; j < KT; ++j) {
+                if (!kFull && j >= jn) break;
+                if (j + 1 < KT && (kFull || j + 1 < jn)) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
+                FATNN_VOP3_RUN_PHASE();
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
         auto compute = [&](int kt, int buf) {
-            {
-                // jn = k-words of this stage that exist (all KT except in the last, partial stage);
-                // the per-word test is a scalar branch
-                const int jn = p.Kw - kt * KT;
-                plane2 w[2][TM], a[2][TN];
-                read_frag(buf, 0, w[0], a[0]);
-#pragma unroll
-                for (int j = 0; j < KT; ++j) {
-                    if (j >= jn) break;
-                    if (j + 1 < KT && j + 1 < jn) read_frag(buf, j + 1, w[(j + 1) & 1], a[(j + 1) & 1]);
-                    FATNN_VOP3_RUN_PHASE();
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int c = 0; c < TN; ++c) acc[i][c].step(w[j & 1][i], a[j & 1][c]);
-                    __builtin_amdgcn_sched_barrier(0);
+            // jn = k-words of this stage that exist (all KT except in the last, partial stage); the per-word
+            // test is a scalar branch.  With the 32 x 32 tile a k-word is only sixteen vector instructions, and
+            // two scalar tests per k-word weigh on it: its full stages run a copy without the tests (512 x N x K
+            // with 1 / 4 / 6 / 8 tiles per compute unit: K = 4608 19.5 -> 13.2, 24.0 -> 20.4, 30.1 -> 27.8,
+            // 38.1 -> 39.4 us; K = 2304 11.4 -> 8.2, 13.7 -> 12.1, 17.2 -> 18.1, 22.9 -> 22.0 us).  The same
+            // copy for the 64 x 64 tile lets the compiler hoist LDS reads (108 instead of 76 registers, four
+            // instead of six wavefronts per SIMD); reading fragments two k-words ahead changes nothing.  The
+            // convolution front end keeps the tests: its three bench layers read 24.1 / 41.4 / 40.0 us with the
+            // copy against 25.0 / 42.1 / 37.0 us without.
+            const int jn = p.Kw - kt * KT;
+            if constexpr (TM * TN <= 4 && !CONV) {
+                if (jn >= KT) {
+                    compute_words(buf, KT, std::true_type{});
+                    return;
                 }
             }
+            compute_words(buf, jn, std::false_type{});
         };
         if constexpr (!kTwoAhead) {
             fetch(kt0, set0);
@@ -484,7 +504,7 @@ __global__ __launch_bounds__(64 * WM * WN, (TM * TN <= 4 ? 8 : 2)) void plane_ge
 
     const int nkt = (p.Kw + KT - 1) / KT;
     if constexpr (!STREAMK) {
-        work_total = nkt;
+        set_work(nkt);
         locate_tile(logical);
         run_stages(0, nkt);
         epilogue();
@@ -492,7 +512,7 @@ __global__ __launch_bounds__(64 * WM * WN, (TM * TN <= 4 ? 8 : 2)) void plane_ge
         if (sk.whole > 0 && logical < sk.whole) {
             // a whole tile of a split-remainder launch: the plain path, kept apart from the bookkeeping of
             // the pieces below so that it runs with the plain kernel's registers
-            work_total = nkt;
+            set_work(nkt);
             locate_tile(logical);
             run_stages(0, nkt);
             epilogue();
@@ -511,7 +531,7 @@ __global__ __launch_bounds__(64 * WM * WN, (TM * TN <= 4 ? 8 : 2)) void plane_ge
         };
         const int u_begin = first_unit(logical), u_end = first_unit(logical + 1);
         if (u_begin >= u_end) return;
-        work_total = u_end - u_begin;
+        set_work(u_end - u_begin);
         const int tile_first = u_begin / nst, tile_last = (u_end - 1) / nst;
         const int nseg = tile_last - tile_first + 1;
         // The piece at the end of the range (the tile is finished by the next workgroup) is done first:
@@ -904,22 +924,23 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
     if (forced >= 1 && forced <= 8) {
         G = (int64_t)cus * forced;
     } else {
-        // Measured (1536^2 x 4096: 44.5 -> 40.8 us, 768^2 x 8192: 34.7 -> 27.9 us, 256^2 x 32768: 112 -> 32 us;
-        // 2048^3 equal; 3072^3, 256 x 12544 x 1152 and 512 x 3136 x 2304 slower): the even shares pay where the
-        // 64 x 64 tiles would not give every compute unit four workgroups and K is long enough (sixteen
-        // stages) to carry the hand-over.
+        // Where the even shares of 64 x 64 tiles beat one 32 x 32 tile per workgroup (measured, us, plain -> even
+        // shares): with few tiles and a long K, where the plain launch is one long chain of load latencies per
+        // workgroup -- 256^2 x 32768 71 -> 32, 512^2 x 16384 37 -> 28, 256 x 2048 x 16384 (two tiles per
+        // compute unit) 44 -> 39, 256 x 3072 x 32768 (three) 100 -> 91; not at K = 8192 (256 x 1024 x 8192
+        // 20.4 -> 20.9, 256 x 3072 x 8192 27.9 -> 30.4) and not at K = 4096 (11.6 -> 16.1).
         const int64_t t32 = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
         if (ntiles >= 4 * (int64_t)cus || nst < 16) return 1;
-        // From two to eight 32 x 32 tiles per compute unit the tile-per-workgroup launch (all tiles resident
-        // at once) is as good or better (1024^2 x 4096: 21.4 against 23.9 us, 768^2 x 4096: 19.3 against 19.9)
-        // until K reaches 32 stages (1024^2 x 8192: 38.9 -> 37.1 us).
-        if (t32 >= 2 * (int64_t)cus && t32 < 8 * (int64_t)cus && nst < 32) return 1;
-        // Beyond eight per unit that launch needs a second round of workgroups; the even shares win where that
-        // round is thin (1536^2 x 4096, one tile per unit left: 44.5 -> 40.8 us) and lose where it is well
-        // filled (1792^2 x 4096, 4.25 left: 52.4 against 54.3 us; 4096 x 512 x 4608, none left: 36.8 against 39.0).
-        if (t32 >= 8 * (int64_t)cus) {
+        if (t32 < 8 * (int64_t)cus) {
+            const bool few_long = (nst >= 64 && t32 <= 2 * (int64_t)cus) || (nst >= 128 && t32 <= 3 * (int64_t)cus);
+            if (!few_long) return 1;
+        } else {
+            // Beyond eight 32 x 32 tiles per compute unit the plain launch needs a second round of workgroups.
+            // K >= 8192: 1536^2 77.1 -> 69.9, 1600^2 82.2 -> 76.2, 1472^2 73.2 -> 66.7.  K = 4096: only where
+            // that round is thin (1536^2, one tile per unit left: 41.2 -> 40.2; 1664^2, 2.6 left: 45.0 -> 46.5;
+            // 1792^2, 4.25 left: 50.0 -> 52.6); never where nothing is left (4096 x 512 x 4608: 38.0 -> 39.0).
             const int64_t left = t32 % (8 * (int64_t)cus);
-            if (left == 0 || left > 3 * (int64_t)cus) return 1;
+            if (left == 0 || left > (nst >= 32 ? 4 : 1) * (int64_t)cus) return 1;
         }
         // About eight stages per workgroup, in whole multiples of the compute units (every unit then runs the
         // same number of equal shares), two to four per unit -- but never more than sixteen pieces per tile
@@ -967,18 +988,21 @@ int launch_split_remainder(const GemmParams& p, hipStream_t stream) {
     if (ntiles > kEvenShareCounterBytes / 4 || ntiles * nst >= 0x7FFFFFFFLL) return 1;
     const int cus = compute_units();
     const int64_t q = ntiles / cus, r = ntiles - q * cus;
-    // Measured on 256 x N x K with N chosen for q = 1..7 and r = 16..192 (times in us, plain launch -> this one):
-    // K = 9216: q >= 2, r <= 128: 38.5 -> 36.0, 48.2 -> 44.2, 68.3 -> 63.3 (5-8 % less), r = 192: 1-3 % less;
-    // K = 4608: the same 4-7 %; K = 2304: 1-6 % less from q = 5 on with r <= 64, 5-15 % more for q <= 3;
-    // K = 1152: 0-35 % more.  The hand-over of the split tiles has to hide behind at least q tiles of work.
-    // At most eight workgroups of these tiles are resident per compute unit, hence q <= 7.
+    // Measured on 256 x N x K with N chosen for q = 1..7 and r = 16..192 (this launch's time over the plain
+    // launch's): K = 9216: 0.88-0.95 for q = 2..6 and r <= 128, 0.96-0.99 at r = 192; K = 4608: 0.91-0.96 for
+    // q = 4, 5, 7 and r <= 128, 0.95-0.985 for q = 3, 1.06 for q = 2 with r <= 32; K = 2304: 0.91 for q = 5,
+    // 0.95 for q = 6 with r <= 64, 1.07-1.36 for q <= 4; K = 1152: 1.0-1.6.  The hand-over of the split tiles
+    // has to hide behind at least q tiles of work.  At most eight workgroups of these tiles are resident per
+    // compute unit, hence q <= 7.
     if (r == 0 || q < 1) return 1;
     if (forced == 0) {
-        if (q < 2 || q > 7) return 1;
-        if (nst >= 16) {
-            if (r > cus / 2) return 1;
+        if (q > 7) return 1;
+        if (nst >= 32) {
+            if (q < 2 || r > cus / 2) return 1;
+        } else if (nst >= 16) {
+            if (q < 3 || r > cus / 2) return 1;
         } else if (nst >= 8) {
-            if (q < 5 || r > cus / 4) return 1;
+            if (q < 5 || q > 6 || r > cus / 4) return 1;
         } else {
             return 1;
         }
@@ -1023,8 +1047,8 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
         int rc = launch_deepk<OP>(p, stream);
         if (rc <= 0) return rc;
         // Three to eight 32 x 32 tiles per compute unit: splitting only the remainder beats the even shares
-        // of 64 x 64 tiles where both apply (1280^2 x 8192: 50.8 against 54.8 us); with fewer tiles the even
-        // shares come first (256 x 2112 x 9216: 29.8 against 36.0 us).
+        // of 64 x 64 tiles where both apply (1280^2 x 8192: 47.5 against 54.8 us); with fewer tiles and a very
+        // long K the even shares come first.
         const int64_t t32 = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
         const int64_t cus = compute_units();
         const bool split_first = t32 >= 3 * cus && t32 < 8 * cus;
