@@ -314,7 +314,8 @@ int fatnn_level_status(int64_t n_invalid_host);
  *   seven_pixel_groups  0 = off, 1 = by the size rule, 2 = wherever a kernel exists
  *   gemm_even_share     schedule of the *_gemm_ws calls: 0 = automatic, 1..8 = even shares with that many
  *                       workgroups per compute unit whatever the size, 9 = never, 10 = whole tiles plus a
- *                       split remainder wherever the tile count is not a multiple of the compute units
+ *                       split remainder wherever the tile count is not a multiple of the compute units,
+ *                       11 = even shares of the small (32 x 32) tile whatever the size
  *   gemm_deepk          kernel for GEMMs with at most 128 columns and K >= 2048 (fully connected layers):
  *                       0 = automatic, 1 = wherever the shape fits, 2 = never
  * Results never depend on these, only the kernel and launch shape chosen.

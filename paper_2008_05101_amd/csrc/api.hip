@@ -30,7 +30,7 @@ struct TuningState {
         u7_mode.store((e != nullptr && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 1);
         e = getenv("FATNN_GEMM_EVEN_SHARE");
         const int es = e != nullptr ? atoi(e) : 0;
-        gemm_even_share.store(es >= 0 && es <= 10 ? es : 0);
+        gemm_even_share.store(es >= 0 && es <= 11 ? es : 0);
         e = getenv("FATNN_GEMM_DEEPK");
         gemm_deepk.store((e != nullptr && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 0);
     }
@@ -790,7 +790,7 @@ int fatnn_probe_hbm(int kind, void* dst, const void* src, size_t bytes, void* sc
 int fatnn_level_status(int64_t n_invalid_host) { return n_invalid_host == 0 ? FATNN_OK : FATNN_ERR_LEVEL; }
 
 int fatnn_set_tuning(int conv_kernel, int stream_wps, int seven_pixel_groups, int gemm_even_share, int gemm_deepk) {
-    if (conv_kernel > 1 || stream_wps > 8 || seven_pixel_groups > 2 || gemm_even_share > 10 || gemm_deepk > 2)
+    if (conv_kernel > 1 || stream_wps > 8 || seven_pixel_groups > 2 || gemm_even_share > 11 || gemm_deepk > 2)
         return FATNN_ERR_UNSUPPORTED;
     fatnn::set_tuning(conv_kernel, stream_wps, seven_pixel_groups, gemm_even_share, gemm_deepk);
     return FATNN_OK;

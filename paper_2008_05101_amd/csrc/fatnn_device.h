@@ -108,7 +108,8 @@ struct Tuning {
     int stream_wps;     // wavefronts per SIMD of the streaming kernel (0 = planned)
     int u7_mode;        // seven-pixel groups: 0 off, 1 by the size rule, 2 wherever a kernel exists
     int gemm_even_share;  // even-share GEMM schedule: 0 automatic, 1..8 workgroups per CU forced, 9 never,
-                          // 10 whole tiles + split remainder wherever there is a remainder
+                          // 10 whole tiles + split remainder wherever there is a remainder, 11 even shares of
+                          // 32 x 32 tiles whatever the size
     int gemm_deepk;       // few-column / long-K kernel: 0 automatic, 1 wherever the shape fits, 2 never
 };
 Tuning tuning();

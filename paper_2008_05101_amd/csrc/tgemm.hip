@@ -917,7 +917,7 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
     const int64_t units = ntiles * nst;
     if (ntiles > kEvenShareCounterBytes / 4 || units >= 0x7FFFFFFFLL) return 1;
     const int forced = always_per_cu > 0 ? always_per_cu : tuning().gemm_even_share;
-    if (forced == 9 || forced == 10) return 1;
+    if (forced == 9 || forced == 10 || forced == 11) return 1;
     const int cus = compute_units();
     const int64_t fit = ((int64_t)p.ws_bytes - kEvenShareCounterBytes) / (2 * kTileBytes);
     int64_t G;
@@ -932,6 +932,7 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
         const int64_t t32 = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
         if (ntiles >= 4 * (int64_t)cus || nst < 16) return 1;
         if (t32 < 8 * (int64_t)cus) {
+            // (with at most two 32 x 32 tiles per compute unit launch_even_share_small is tried first and wins)
             const bool few_long = (nst >= 64 && t32 <= 2 * (int64_t)cus) || (nst >= 128 && t32 <= 3 * (int64_t)cus);
             if (!few_long) return 1;
         } else {
@@ -966,6 +967,50 @@ int launch_even_share(const GemmParams& p, hipStream_t stream, const int always_
     set_shares(sk, G);
     const LaunchTiming t = take_launch_timing();
     hipExtLaunchKernelGGL((plane_gemm_kernel<OP, WM, WN, TM, TN, false, true>), dim3((unsigned)G), dim3(NT), 0, stream,
+                          t.start, t.stop, 0, p, tiles_m, (int)ntiles, sk);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Even shares of 32 x 32 tiles: for GEMMs with at most two of these tiles per compute unit and a long K, where
+// a tile per workgroup is one long chain of load latencies on a mostly idle chip.  The shares are those of
+// launch_even_share; the tile is the small one because its pieces hand over a quarter of the partial sums
+// and its K loop runs the stages without tail tests.  Measured against the better of the plain launch and
+// the 64 x 64 shares (us): 128 x 512 x 8192 20.3 -> 13.3, 256 x 1024 x 8192 20.3 -> 16.7, 256 x 2048 x 8192
+// 23.6 -> 21.7 (256 x 3072 x 8192: 27.8 -> 28.3, not taken); 128 x 512 x 16384 24.9 -> 17.4, 256 x 1024 x 16384
+// 28.2 -> 24.4, 256 x 2048 x 16384 38.9 -> 36.1; 128 x 512 x 32768 31.5 -> 25.2, 256 x 1024 x 32768 44.7 -> 38.4;
+// nothing to gain at K = 4096.  About sixteen stages per workgroup, one to four workgroups per compute unit
+// (128 x 512 x 16384 with 1 / 2 / 4 per unit: 17.4 / 20.7 / 32.7; 256 x 1024 x 16384: 36.7 / 26.3 / 24.4).
+// Returns 0 = launched, 1 = not applicable, -1 = launch error.
+template <int OP>
+int launch_even_share_small(const GemmParams& p, hipStream_t stream) {
+    constexpr int NT = 256, BM = 32, BN = 32;
+    constexpr int64_t kTileBytes = (int64_t)2 * 2 * Acc<OP>::kWords * NT * 4;
+    if (p.ws == nullptr || p.ws_bytes <= (size_t)kEvenShareCounterBytes) return 1;
+    const int forced = tuning().gemm_even_share;
+    if (forced != 0 && forced != 11) return 1;
+    const int tiles_m = (p.M + BM - 1) / BM;
+    const int64_t ntiles = (int64_t)tiles_m * (((int64_t)p.N + BN - 1) / BN);
+    const int nst = (p.Kw + KT - 1) / KT;
+    const int64_t units = ntiles * nst;
+    if (ntiles > kEvenShareCounterBytes / 4 || units >= 0x7FFFFFFFLL) return 1;
+    const int64_t cus = compute_units();
+    if (forced == 0 && (nst < 32 || ntiles > 2 * cus)) return 1;
+    int64_t per_cu = (units + 16 * cus - 1) / (16 * cus);
+    per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+    int64_t G = cus * per_cu;
+    if (G > units / 4) G = units / 4;   // at least four stages each
+    G = (G + 7) & ~(int64_t)7;
+    const int64_t fit = ((int64_t)p.ws_bytes - kEvenShareCounterBytes) / (2 * kTileBytes);
+    if (G > fit) G = fit & ~(int64_t)7;
+    if (G < 8) return 1;
+    StreamKArgs sk{};
+    sk.counters = reinterpret_cast<int32_t*>(p.ws);
+    sk.partial = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.ws) + kEvenShareCounterBytes);
+    sk.nst = nst;
+    sk.units = (int32_t)units;
+    set_shares(sk, G);
+    const LaunchTiming t = take_launch_timing();
+    hipExtLaunchKernelGGL((plane_gemm_kernel<OP, 2, 2, 2, 2, false, true>), dim3((unsigned)G), dim3(NT), 0, stream,
                           t.start, t.stop, 0, p, tiles_m, (int)ntiles, sk);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -1052,6 +1097,10 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
         const int64_t t32 = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
         const int64_t cus = compute_units();
         const bool split_first = t32 >= 3 * cus && t32 < 8 * cus;
+        if (wave_tiles < 1024) {
+            rc = launch_even_share_small<OP>(p, stream);
+            if (rc <= 0) return rc;
+        }
         if (split_first) {
             rc = launch_split_remainder<OP, 2, 2>(p, stream);
             if (rc <= 0) return rc;

@@ -160,6 +160,49 @@ def test_split_remainder_twobit_and_binary_operators(tuning):
     assert counters_are_zero(fatnn.gemm_workspace(DEV))
 
 
+# ----------------------------------------------------------------------------- even shares of 32 x 32 tiles
+@pytest.mark.parametrize("M,N,K,mode", [(128, 512, 8192, 0),       # the automatic choice: 64 tiles, long K
+                                        (256, 1024, 16384, 1),     # one tile per compute unit
+                                        (100, 300, 9000, 0),       # ragged M, N and K
+                                        (512, 3136, 4609, 1),      # forced only: 1568 tiles, four shares per unit
+                                        (32, 32, 65536, 0),        # one tile shared by many
+                                        (640, 640, 300, 1)])       # two stages per tile
+def test_small_tile_even_shares_match_oracle(tuning, M, N, K, mode):
+    rnd = np.random.default_rng(3 * M + N + K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    scale = rnd.uniform(0.5, 1.5, M).astype(np.float32)
+    bias = rnd.standard_normal(M).astype(np.float32)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    Ap = fatnn.pack_ternary(dev(La), fatnn.ACT)
+    ws = fatnn.gemm_workspace(DEV)
+    want = oracle.ternary_gemm(Lw, La, mode)
+    wantf = oracle.scale_epilogue(want, scale, bias, channel_is_row=True)
+    for setting in (11, 0):
+        tuning(gemm_even_share=setting, gemm_deepk=2)
+        for _ in range(2):
+            C, Cf = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode, scale=dev(scale), bias=dev(bias), workspace=ws)
+            assert np.array_equal(C.cpu().numpy(), want)
+            assert np.array_equal(Cf.cpu().numpy(), wantf)
+            assert counters_are_zero(ws)
+
+
+def test_small_tile_even_shares_twobit_and_binary_operators(tuning):
+    tuning(gemm_even_share=11, gemm_deepk=2)
+    rnd = np.random.default_rng(1111)
+    M, N, K = 200, 330, 5000
+    Qw = rnd.integers(0, 4, size=(M, K), dtype=np.int8)
+    Qa = rnd.integers(0, 4, size=(N, K), dtype=np.int8)
+    for basis in (0, 1):
+        C = fatnn.twobit_gemm(fatnn.pack_twobit(dev(Qw)), fatnn.pack_twobit(dev(Qa)), M, N, K, basis)
+        assert np.array_equal(C.cpu().numpy(), oracle.twobit_gemm(Qw, Qa, basis))
+    Bw = rnd.integers(0, 2, size=(M, 2 * K + 5), dtype=np.int8)
+    Ba = rnd.integers(0, 2, size=(N, 2 * K + 5), dtype=np.int8)
+    Cb = fatnn.binary_gemm(fatnn.pack_binary(dev(Bw)), fatnn.pack_binary(dev(Ba)), M, N, 2 * K + 5)
+    assert np.array_equal(Cb.cpu().numpy(), oracle.binary_gemm(Bw, Ba))
+    assert counters_are_zero(fatnn.gemm_workspace(DEV))
+
+
 # ----------------------------------------------------------------------------- few columns, long K
 @pytest.mark.parametrize("M,N,K,mode", [(4096, 17, 4608, 0), (4096, 32, 4608, 1), (4096, 64, 4608, 0),
                                         (4096, 128, 4608, 1), (1000, 100, 9216, 0), (70, 33, 2048, 1),
@@ -208,7 +251,8 @@ def test_deepk_kernel_twobit_and_binary_operators(tuning):
 
 
 @pytest.mark.parametrize("per_cu,M,N,K", [(8, 4096, 32, 4608), (4, 512, 3136, 4609), (3, 640, 640, 16384),
-                                          (10, 512, 3136, 4609), (10, 32, 8224, 8192)])
+                                          (10, 512, 3136, 4609), (10, 32, 8224, 8192), (11, 128, 512, 16384),
+                                          (11, 32, 64, 65536)])
 def test_even_share_hand_over_is_stable_over_many_calls(tuning, per_cu, M, N, K):
     """The hand-over between workgroups (write-through stores, counter, device-scope loads) has no ordering
     slack: 300 calls in a row, many pieces per tile, every result equal to the oracle's."""

@@ -82,7 +82,7 @@ def test_level_status_and_tuning_arguments(lib):
     assert lib.fatnn_set_tuning(2, 0, 1, 0, 0) == -6
     assert lib.fatnn_set_tuning(0, 9, 1, 0, 0) == -6
     assert lib.fatnn_set_tuning(0, 0, 3, 0, 0) == -6
-    assert lib.fatnn_set_tuning(0, 0, 1, 11, 0) == -6
+    assert lib.fatnn_set_tuning(0, 0, 1, 12, 0) == -6
     assert lib.fatnn_set_tuning(0, 0, 1, 0, 3) == -6
     assert lib.fatnn_set_tuning(0, 0, 1, 0, 0) == 0
 
