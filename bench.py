@@ -508,9 +508,9 @@ def side_workload(args, torch, fatnn, si, dev):
         print(json.dumps(line))
         return
     if args.workload == "midgemm":
-        # GEMMs whose tiles do not fill the chip evenly: the ragged cfg5 GEMM, two square ones with a long K (even-share
-        # schedule) and fully connected layers at batch 16-128 (K-splitting kernel); each against the plain call
-        shapes = [(512, 3136, 4609), (1536, 1536, 4096), (768, 768, 8192), (4096, 16, 4608), (4096, 32, 4608),
+        # GEMMs whose tiles do not fill the chip evenly: the ragged cfg5 GEMM, three square ones with a long K (the
+        # even-share schedules) and fully connected layers at batch 16-128 (K-splitting kernel); each against the plain call
+        shapes = [(512, 3136, 4609), (1536, 1536, 4096), (768, 768, 8192), (256, 256, 32768), (4096, 16, 4608), (4096, 32, 4608),
                   (4096, 64, 4608), (4096, 128, 4608)]
         results = {}
         tot_ms = tot_ops = 0.0
@@ -540,8 +540,8 @@ def side_workload(args, torch, fatnn, si, dev):
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
             "config": {"workload": "midgemm: ternary GEMMs whose tiles do not fill 256 compute units evenly "
-                                   "(512x3136x4609, 1536^2x4096, 768^2x8192) and fully connected layers "
-                                   "4096xNx4608 at N = 16..128; operands already packed; value = all seven in a row"},
+                                   "(512x3136x4609, 1536^2x4096, 768^2x8192, 256^2x32768) and fully connected layers "
+                                   "4096xNx4608 at N = 16..128; operands already packed; value = all eight in a row"},
             "roofline": alu_roofline(f"GEMM {best[1]}", best[0] / 1e9, best[2], peaks, None),
             "cpu_baseline": None, "extra": results,
         }
