@@ -262,8 +262,9 @@ int fatnn_binary_gemm(const void *Wb, const void *Ab, int64_t M, int64_t N, int6
  * The three GEMM calls above with a workspace, for problems whose tiles do not fill the 256 compute units
  * evenly (a few hundred tiles, or few tiles with a long K: fully connected layers at batch 17-128, which
  * Supplementary S1 treats as convolutions whose filter covers the whole feature map).  Same arguments,
- * results identical bit for bit; with the workspace the library may cut the K loops of the tiles into
- * equal shares for all workgroups and combine the partial popcount sums of Eq. 3 through it.
+ * results identical bit for bit; with the workspace the library may cut the K loops of all tiles, or of the
+ * tiles left over after whole rounds on the compute units, into equal shares for the workgroups and combine
+ * the partial popcount sums of Eq. 3 through it.
  *   workspace        device, 16-byte aligned, or NULL (then exactly the plain call)
  *   workspace_bytes  any size; fatnn_gemm_workspace_bytes() lets every shape use the full schedule, a
  *                    smaller one limits the number of workgroups, one below 128 KiB is not used at all
