@@ -117,6 +117,51 @@ def test_chain_epilogue_nan_and_inf_in_the_skip(relu, out_mode):
     assert np.array_equal(interior, lv_want)
 
 
+@pytest.mark.parametrize("relu", [True, False])
+@pytest.mark.parametrize("out_mode", [0, 1])
+@pytest.mark.parametrize("with_f", [True, False])
+def test_chain_epilogue_unusual_channel_coefficients(relu, out_mode, with_f):
+    """Per-channel scale and bias that are negative, zero, denormal, huge, infinite or NaN (the paper fixes one
+    positive scale per layer; the library takes whatever float it is given and must follow the float32
+    definition of the epilogue for all of them), with and without the fp32 output."""
+    rnd = np.random.default_rng(77 + relu + 2 * out_mode)
+    B, Cin, Cout, H, W = 2, 64, 128, 5, 9
+    Lw = rnd.integers(0, 3, size=(Cout, 3, 3, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(B, H, W, Cin), dtype=np.int8)
+    C = oracle.ternary_conv2d(Lw, Lx, 1, 1, 1)
+    scale = (rnd.uniform(0.5, 1.5, Cout) / (float(C.std()) + 1.0)).astype(np.float32)
+    bias = (rnd.standard_normal(Cout) * 0.3).astype(np.float32)
+    scale[0:8] *= -1.0
+    scale[8:12] = 0.0
+    scale[12:14] = -0.0
+    scale[14] = np.float32(1e-42)              # denormal
+    scale[15] = np.float32(3e38)               # products overflow
+    scale[16] = np.inf
+    scale[17] = -np.inf
+    scale[18] = np.nan
+    bias[20] = np.inf
+    bias[21] = -np.inf
+    bias[22] = np.nan
+    bias[23] = np.float32(-3e38)
+    bias[16] = -np.inf                         # inf - inf
+    skip = (rnd.standard_normal((B, H, W, Cout)) * 0.5).astype(np.float32)
+    bias[14] = 0.0
+    skip[..., 14] = 0.0                        # the denormal products of channel 14 reach the output as they are
+    with np.errstate(all="ignore"):
+        f_want, lv_want = ochain.chain_epilogue(C, scale, bias, skip, relu, out_mode, 0.6, 0.8)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT, fatnn.OHWI)
+    Xp = fatnn.pack_ternary_bordered(dev(Lx), 1, 1)
+    Xn = fatnn.bordered_act_init(B, H, W, Cout, 1, out_mode, device=DEV)
+    Yf = torch.empty((B, H, W, Cout), dtype=torch.float32, device=DEV) if with_f else None
+    fatnn.ternary_conv2d_chain(Wp, Xp, B, Cin, H, W, Cout, 3, 3, 1, 1, 1, dev(scale), dev(bias), dev(skip), relu,
+                               0.6, 0.8, out_mode, 1, Xn, out_f=Yf)
+    torch.cuda.synchronize()
+    if with_f:
+        assert np.array_equal(Yf.cpu().numpy(), f_want, equal_nan=True)
+    interior, _, _ = decode_bordered(Xn, B, H, W, Cout, 1)
+    assert np.array_equal(interior, lv_want)
+
+
 @pytest.mark.parametrize("Cin,Cout,H,W,use_skip", [(128, 256, 9, 14, True), (256, 512, 6, 14, False)])
 def test_chain_epilogue_stride2_groups_of_seven(tuning, Cin, Cout, H, W, use_skip):
     tuning(seven_pixel_groups=2)

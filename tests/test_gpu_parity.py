@@ -296,6 +296,60 @@ def test_gemm_scale_epilogue():
     assert np.array_equal(Cf.cpu().numpy(), oracle.scale_epilogue(C, scale, None, True))
 
 
+def unusual_coefficients(rnd, M):
+    """Scale and bias vectors with negative, zero, denormal, huge, infinite and NaN entries."""
+    scale = si.scale_vec(rnd, M)
+    bias = si.bias_vec(rnd, M)
+    scale[0:4] *= -1.0
+    scale[4] = 0.0
+    scale[5] = -0.0
+    scale[6] = np.float32(1e-42)
+    scale[7] = np.float32(3e38)
+    scale[8] = np.inf
+    scale[9] = -np.inf
+    scale[10] = np.nan
+    bias[6] = 0.0
+    bias[8] = -np.inf
+    bias[12] = np.inf
+    bias[13] = np.nan
+    bias[14] = np.float32(-3e38)
+    return scale, bias
+
+
+@pytest.mark.parametrize("M,N,K", [(70, 90, 500),         # tiled kernel
+                                   (64, 3, 4608),         # matrix-vector kernel
+                                   (96, 40, 4096),        # K-splitting kernel
+                                   (128, 512, 8192)])     # even shares (hand-over before the epilogue)
+def test_gemm_scale_epilogue_unusual_coefficients(M, N, K):
+    """The fp32 epilogue is float32 multiply-then-add for every float it is given (the paper fixes one positive
+    scale; the library does not check it): equal to the oracle bit for bit, NaN for NaN."""
+    rnd = np.random.default_rng(M + N + K)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+    scale, bias = unusual_coefficients(rnd, M)
+    C = oracle.ternary_gemm(Lw, La, 0)
+    with np.errstate(all="ignore"):
+        want = oracle.scale_epilogue(C, scale, bias, channel_is_row=True)
+    Ci, Cf = gemm_gpu(Lw, La, 0, scale=dev(scale), bias=dev(bias))
+    assert np.array_equal(Ci.cpu().numpy(), C)
+    assert np.array_equal(Cf.cpu().numpy(), want, equal_nan=True)
+
+
+@pytest.mark.parametrize("bordered", [True, False])
+def test_conv_scale_epilogue_unusual_coefficients(bordered):
+    rnd = np.random.default_rng(31 + bordered)
+    B, Cin, Cout, H, W = 2, 64, 64, 7, 9
+    Lw = rnd.integers(0, 3, size=(Cout, 3, 3, Cin), dtype=np.int8)
+    Lx = rnd.integers(0, 3, size=(B, H, W, Cin), dtype=np.int8)
+    scale, bias = unusual_coefficients(rnd, Cout)
+    Y = oracle.ternary_conv2d(Lw, Lx, 1, 1, 1)
+    with np.errstate(all="ignore"):
+        want = oracle.scale_epilogue(Y, scale, bias, channel_is_row=False)
+    Yi, Yf = conv_gpu(Lw, Lx, 1, 1, 1, bordered=bordered, scale=dev(scale), bias=dev(bias))
+    assert np.array_equal(Yi.cpu().numpy(), Y)
+    assert np.array_equal(Yf.cpu().numpy(), want, equal_nan=True)
+
+
 # ----------------------------------------------------------------------------- convolution
 @pytest.mark.parametrize("Cin,Cout,H,W,R,stride,pad", [
     (32, 5, 6, 7, 3, 1, 1), (64, 64, 9, 9, 3, 1, 1), (64, 70, 12, 10, 3, 2, 1), (96, 33, 8, 8, 3, 1, 1),
