@@ -12,13 +12,16 @@ pytestmark = pytest.mark.gpu
 
 fatnn = pytest.importorskip("paper_2008_05101_amd")
 
-ALPHAS = [(0.7, 0.9), (1.3, 0.2), (0.05, 2.5), (0.5, 0.25), (1.0, 1.0), (3.1415927, 0.33333334)]
+ALPHAS = [(0.7, 0.9), (1.3, 0.2), (0.05, 2.5), (0.5, 0.25), (1.0, 1.0), (3.1415927, 0.33333334),
+          # step sizes far from one: tiny, a second step below the first one's rounding unit, denormal, near overflow
+          (1e-30, 3e-30), (1e30, 1e-30), (1e-40, 1e-40), (3e38, 3e38)]
 
 
 def adversarial(rnd, n, a1, a2):
     """Random normals plus clouds of floats within +-8 ulps of every real-number threshold."""
     x = (rnd.standard_normal(n) * 1.5).astype(np.float32)
-    centres = np.array([-a1 / 2, a2 / 2, a1 / 2, a1 + a2 / 2, 0.0, -0.0, a1, a2], np.float32)
+    with np.errstate(over="ignore"):              # a1 + a2 / 2 may round to +inf (step sizes near overflow)
+        centres = np.array([-a1 / 2, a2 / 2, a1 / 2, a1 + a2 / 2, 0.0, -0.0, a1, a2], np.float32)
     pos = rnd.choice(n, size=min(n, 64 * len(centres)), replace=False)
     k = 0
     for c in centres:
