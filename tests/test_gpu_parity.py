@@ -296,6 +296,59 @@ def test_gemm_scale_epilogue():
     assert np.array_equal(Cf.cpu().numpy(), oracle.scale_epilogue(C, scale, None, True))
 
 
+def test_gemm_operands_beyond_4_gib():
+    """Packed operands larger than 4 GiB in either role (2^20 + 77 rows of K = 16416): the kernels address a
+    tile's rows from a 64-bit tile base with 32-bit offsets, the packing kernels with 64-bit indices.  Outputs
+    are compared with the oracle on columns / rows from both ends and the middle of the big operand."""
+    M, N, K = 48, (1 << 20) + 77, 16384 + 32
+    g = torch.Generator(device=DEV).manual_seed(5)
+    La = torch.randint(0, 3, (N, K), dtype=torch.int8, device=DEV, generator=g)
+    Lw = torch.randint(0, 3, (M, K), dtype=torch.int8, device=DEV, generator=g)
+    Lw_h = Lw.cpu().numpy()
+    pick = torch.from_numpy(np.concatenate([np.arange(0, 40), np.arange(N // 2 - 20, N // 2 + 20),
+                                            np.arange(N - 100, N)])).to(DEV)
+    La_h = La[pick].cpu().numpy()
+    Ap = fatnn.pack_ternary(La, fatnn.ACT)
+    assert Ap.numel() > (1 << 32)
+    Wp = fatnn.pack_ternary(Lw, fatnn.WEIGHT)
+    for mode in (0, 1):
+        C, _ = fatnn.ternary_gemm(Wp, Ap, M, N, K, mode)
+        assert np.array_equal(C[:, pick].cpu().numpy(), oracle.ternary_gemm(Lw_h, La_h, mode))
+    del Ap, C
+    Wbig = fatnn.pack_ternary(La, fatnn.WEIGHT)
+    del La
+    Asmall = fatnn.pack_ternary(Lw, fatnn.ACT)
+    C, _ = fatnn.ternary_gemm(Wbig, Asmall, N, M, K, 0)
+    assert np.array_equal(C[pick].cpu().numpy(), oracle.ternary_gemm(La_h, Lw_h, 0))
+    del Wbig, C
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("bordered", [True, False])
+def test_conv_output_beyond_4_gib(bordered):
+    """A 1x1 convolution whose int32 output is 4.5 GB (batch 1400 of 56 x 56 x 64 -> 256): the streaming kernel
+    addresses its output with 32-bit offsets, so the call must go to the tiled kernel (64-bit output
+    addressing) whatever the input layout.  Three images are compared with the oracle."""
+    B, Cin, Cout, H, W = 1400, 64, 256, 56, 56
+    g = torch.Generator(device=DEV).manual_seed(9)
+    Lx = torch.randint(0, 3, (B, H, W, Cin), dtype=torch.int8, device=DEV, generator=g)
+    Lw = torch.randint(0, 3, (Cout, 1, 1, Cin), dtype=torch.int8, device=DEV, generator=g)
+    Wp = fatnn.pack_ternary(Lw, fatnn.WEIGHT, fatnn.OHWI)
+    if bordered:
+        Xp = fatnn.pack_ternary_bordered(Lx, 0, 1)
+        Y, _ = fatnn.ternary_conv2d(Wp, Xp, B, Cin, H, W, Cout, 1, 1, 1, 0, 1, x_layout=fatnn.X_BORDERED)
+    else:
+        Xp = fatnn.pack_ternary(Lx, fatnn.ACT, fatnn.NHWC)
+        Y, _ = fatnn.ternary_conv2d(Wp, Xp, B, Cin, H, W, Cout, 1, 1, 1, 0, 1)
+    assert Y.numel() * 4 > (1 << 32)
+    Lw_h = Lw.cpu().numpy()
+    for b in (0, 700, B - 1):
+        want = oracle.ternary_conv2d(Lw_h, Lx[b:b + 1].cpu().numpy(), 1, 0, 1)
+        assert np.array_equal(Y[b:b + 1].cpu().numpy(), want)
+    del Y, Xp, Lx
+    torch.cuda.empty_cache()
+
+
 def unusual_coefficients(rnd, M):
     """Scale and bias vectors with negative, zero, denormal, huge, infinite and NaN entries."""
     scale = si.scale_vec(rnd, M)
