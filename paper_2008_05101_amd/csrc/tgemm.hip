@@ -1112,7 +1112,20 @@ int launch_op(const GemmParams& p, hipStream_t stream) {
             if (rc <= 0) return rc;
         }
     }
-    if (wave_tiles >= 1024) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
+    // One tile per workgroup: the middle tile (64 x 64 for the one-word operators) or the 32 x 32 tile.  Fully
+    // balanced, the middle tile is about 10 % faster (2048^3 33.1 against 36.6 us, 3072^3 94.3 against 104.6),
+    // but a compute unit runs whole tiles, ceil(tiles / CUs) of them on the busiest unit, and that rounding
+    // costs the larger tile more: 2560^3 (6.25 middle tiles per unit) 70.9 against 63.9 us, 512 x 12544 x 2304
+    // (6.125) 62.7 against 57.8, 1792^2 x 4096 (3.06) 58.1 against 50.6; 1536 x 2048 x 2048 (3 exactly) 27.1
+    // against 29.0.  Below three middle tiles per unit the small tile keeps more wavefronts at work
+    // (2048 x 1024 x 8192, two per unit: 69.5 against 61.0 us).
+    const int64_t units_cu = compute_units();
+    const int64_t t_small = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 31) / 32);
+    auto busiest_over_mean = [&](int64_t tiles) {
+        return (double)(((tiles + units_cu - 1) / units_cu) * units_cu) / (double)tiles;
+    };
+    const bool middle = wave_tiles >= 3 * units_cu && busiest_over_mean(wave_tiles) <= 1.10 * busiest_over_mean(t_small);
+    if (middle) return launch_shape<OP, 2, 2, TM / 2, TN / 2>(p, stream);
     return launch_shape<OP, 2, 2, 2, 2>(p, stream);
 }
 
