@@ -203,6 +203,41 @@ def test_small_tile_even_shares_twobit_and_binary_operators(tuning):
     assert counters_are_zero(fatnn.gemm_workspace(DEV))
 
 
+@pytest.mark.parametrize("setting,M,N,K", [(0, 512, 3136, 4609),     # whole tiles plus a split remainder
+                                           (0, 128, 512, 8192),      # even shares of 32 x 32 tiles
+                                           (4, 300, 500, 2000)])     # even shares of 64 x 64 tiles
+def test_workspace_schedules_in_a_captured_graph(tuning, setting, M, N, K):
+    """pack + GEMM with a workspace captured into a HIP graph: every replay (new activations each time, eager
+    calls on the same workspace in between) equals the oracle; the schedules clear their own counters, no
+    memset node is recorded."""
+    tuning(gemm_even_share=setting, gemm_deepk=2)
+    rnd = np.random.default_rng(M + K + setting)
+    Lw = rnd.integers(0, 3, size=(M, K), dtype=np.int8)
+    Wp = fatnn.pack_ternary(dev(Lw), fatnn.WEIGHT)
+    La_d = torch.zeros((N, K), dtype=torch.int8, device=DEV)
+    Ap = fatnn.pack_ternary(La_d, fatnn.ACT)
+    ws = fatnn.gemm_workspace(DEV)
+    C = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    fatnn.ternary_gemm(Wp, Ap, M, N, K, 0, out=C, workspace=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fatnn.pack_ternary(La_d, fatnn.ACT, out=Ap)
+        fatnn.ternary_gemm(Wp, Ap, M, N, K, 0, out=C, workspace=ws)
+    for rep in range(4):
+        La = rnd.integers(0, 3, size=(N, K), dtype=np.int8)
+        La_d.copy_(dev(La))
+        want = oracle.ternary_gemm(Lw, La, 0)
+        C.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), want), rep
+        C2, _ = fatnn.ternary_gemm(Wp, Ap, M, N, K, 1, workspace=ws)       # eager, other mode, same workspace
+        assert np.array_equal(C2.cpu().numpy(), oracle.ternary_gemm(Lw, La, 1))
+        assert counters_are_zero(ws)
+
+
 # ----------------------------------------------------------------------------- few columns, long K
 @pytest.mark.parametrize("M,N,K,mode", [(4096, 17, 4608, 0), (4096, 32, 4608, 1), (4096, 64, 4608, 0),
                                         (4096, 128, 4608, 1), (1000, 100, 9216, 0), (70, 33, 2048, 1),
